@@ -1,0 +1,276 @@
+// CPU oracle for the expert-specific MoE FFN layer.  TEST INFRASTRUCTURE ONLY.
+//
+// A plain, slow loop nest over one token and one of its experts at a time, in
+// fp64.  It is the definition the GPU library is checked against and shares no
+// code with it.  Only tests, the smoke check and the benchmark's CPU-baseline
+// leg may call this; the product path never does.
+//
+// What it follows (HEXA-MoE, arXiv 2411.01288):
+//   * operator definitions ESMM / ESS / ESTMM            -- Sec. 3.1, items 1-3
+//   * forward  rows 1-3 and backward rows 4-10 of the top-k column of the
+//     "top-1 vs top-k" table                               -- App. B, Table 5
+//   * re-index vector construction                         -- App. B, Alg. 1
+// Readings taken where the paper is silent or garbled:
+//   * gate weights (absent from the paper's formulas) multiply each expert's
+//     output after the 2nd MLP's bias: y_t = sum_j g_tj * (h W2 + b2).  With
+//     g == 1 this is Table 5 row 3 as printed.
+//   * Table 5 row 5 is the 2nd MLP's weight gradient,
+//     dW2 = sum_i ESTMM(y2^i, dl/dy, R_i)  (the printed row repeats row 9).
+//   * the activation F is GELU in its tanh form, constants sqrt(2/pi), 0.044715.
+//   * Alg. 1 leaves the order inside an expert's segment to the atomics; the
+//     canonical order here is ascending flat assignment id a = t*k + j, and
+//     segments carry no padding (the -1 padded form is a derived view).
+//   * Alg. 3/4 recover the expert id through the re-index vector, which is
+//     undefined for an expert with no tokens; here the expert id is the loop
+//     index and such experts get exact zero gradients.
+//   * top-k is one index over the T*k (token, slot) pairs instead of k
+//     separate re-index vectors: same sums.
+//
+// Pins (tests/test_oracle_pins.py): dense all-experts-then-mask brute force in
+// numpy, central finite differences of every input, the E=1 case against a
+// library 2-layer MLP, structural invariants.  No function here is unpinned.
+//
+// All pointers are host memory, dense row-major.  Inputs are float (bf16
+// workloads pass their values widened, which is exact); every sum runs in
+// double and results are returned as double.
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <vector>
+
+namespace {
+
+const double kC = 0.79788456080286535588;  // sqrt(2/pi)
+const double kA = 0.044715;
+
+inline double gelu(double u) {
+    return 0.5 * u * (1.0 + std::tanh(kC * (u + kA * u * u * u)));
+}
+
+inline double gelu_grad(double u) {
+    const double s = kC * (u + kA * u * u * u);
+    const double th = std::tanh(s);
+    return 0.5 * (1.0 + th) + 0.5 * u * (1.0 - th * th) * kC * (1.0 + 3.0 * kA * u * u);
+}
+
+struct Dims { int T, d, f, E, k; };
+
+// pre[n] = b1[e][n] + sum_i x[i] W1[e][i][n]            (ESMM, Table 5 row 1)
+void first_mlp(const Dims& D, const float* xt, const float* W1e, const float* b1e,
+               std::vector<double>& pre) {
+    for (int n = 0; n < D.f; ++n) pre[n] = (double)b1e[n];
+    for (int i = 0; i < D.d; ++i) {
+        const double xi = (double)xt[i];
+        const float* w = W1e + (size_t)i * D.f;
+        for (int n = 0; n < D.f; ++n) pre[n] += xi * (double)w[n];
+    }
+}
+
+// o[m] = b2[e][m] + sum_n h[n] W2[e][n][m]              (ESMM, Table 5 row 3)
+void second_mlp(const Dims& D, const std::vector<double>& h, const float* W2e,
+                const float* b2e, std::vector<double>& o) {
+    for (int m = 0; m < D.d; ++m) o[m] = (double)b2e[m];
+    for (int n = 0; n < D.f; ++n) {
+        const double hn = h[n];
+        const float* w = W2e + (size_t)n * D.d;
+        for (int m = 0; m < D.d; ++m) o[m] += hn * (double)w[m];
+    }
+}
+
+bool bad_dims(const Dims& D) {
+    return D.T <= 0 || D.d <= 0 || D.f <= 0 || D.E <= 0 || D.k <= 0;
+}
+
+bool bad_routing(const Dims& D, const int32_t* idx) {
+    for (size_t a = 0; a < (size_t)D.T * D.k; ++a)
+        if (idx[a] < 0 || idx[a] >= D.E) return true;
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+// App. B Alg. 1, unpadded and stable: counts, exclusive offsets, the re-index
+// vector perm (flat assignment ids grouped by expert, ascending inside each
+// group) and its inverse.  Returns 0, or 1 on an expert id outside [0, E).
+int hexa_oracle_index(int T, int k, int E, const int32_t* topk_idx, int32_t* counts,
+                      int32_t* offsets, int32_t* perm, int32_t* inv) {
+    Dims D{T, 1, 1, E, k};
+    if (bad_dims(D) || bad_routing(D, topk_idx)) return 1;
+    const int A = T * k;
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    for (int a = 0; a < A; ++a) counts[topk_idx[a]]++;
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    std::vector<int32_t> cursor(offsets, offsets + E);
+    for (int a = 0; a < A; ++a) {
+        const int p = cursor[topk_idx[a]]++;
+        perm[p] = a;
+        inv[a] = p;
+    }
+    return 0;
+}
+
+// Forward for the listed tokens (tokens == NULL: all T, n_tokens ignored).
+// y_out is [n][d]; row r belongs to token tokens[r].
+int hexa_oracle_fwd(int T, int d, int f, int E, int k, const float* x, const int32_t* topk_idx,
+                    const float* gate, const float* W1, const float* b1, const float* W2,
+                    const float* b2, const int32_t* tokens, int n_tokens, double* y_out) {
+    Dims D{T, d, f, E, k};
+    if (bad_dims(D) || bad_routing(D, topk_idx)) return 1;
+    const int n = tokens ? n_tokens : T;
+#pragma omp parallel
+    {
+        std::vector<double> pre(f), h(f), o(d);
+#pragma omp for schedule(dynamic, 4)
+        for (int r = 0; r < n; ++r) {
+            const int t = tokens ? tokens[r] : r;
+            double* y = y_out + (size_t)r * d;
+            for (int m = 0; m < d; ++m) y[m] = 0.0;
+            for (int j = 0; j < k; ++j) {
+                const int e = topk_idx[(size_t)t * k + j];
+                const double g = (double)gate[(size_t)t * k + j];
+                first_mlp(D, x + (size_t)t * d, W1 + (size_t)e * d * f, b1 + (size_t)e * f, pre);
+                for (int q = 0; q < f; ++q) h[q] = gelu(pre[q]);                 // row 2
+                second_mlp(D, h, W2 + (size_t)e * f * d, b2 + (size_t)e * d, o);
+                for (int m = 0; m < d; ++m) y[m] += g * o[m];                    // sum over the k slots
+            }
+        }
+    }
+    return 0;
+}
+
+// Backward, per-token outputs: dx [n][d] (Table 5 row 10) and dgate [n][k]
+// (dgate_tj = <dY_t, o_tj>; the router's gradient, outside the paper's table).
+int hexa_oracle_bwd_tokens(int T, int d, int f, int E, int k, const float* x,
+                           const int32_t* topk_idx, const float* gate, const float* W1,
+                           const float* b1, const float* W2, const float* b2, const float* dY,
+                           const int32_t* tokens, int n_tokens, double* dx_out,
+                           double* dgate_out) {
+    Dims D{T, d, f, E, k};
+    if (bad_dims(D) || bad_routing(D, topk_idx)) return 1;
+    const int n = tokens ? n_tokens : T;
+#pragma omp parallel
+    {
+        std::vector<double> pre(f), h(f), o(d), dob(d), dpre(f);
+#pragma omp for schedule(dynamic, 4)
+        for (int r = 0; r < n; ++r) {
+            const int t = tokens ? tokens[r] : r;
+            double* dx = dx_out + (size_t)r * d;
+            for (int i = 0; i < d; ++i) dx[i] = 0.0;
+            for (int j = 0; j < k; ++j) {
+                const int e = topk_idx[(size_t)t * k + j];
+                const double g = (double)gate[(size_t)t * k + j];
+                const float* W1e = W1 + (size_t)e * d * f;
+                const float* W2e = W2 + (size_t)e * f * d;
+                first_mlp(D, x + (size_t)t * d, W1e, b1 + (size_t)e * f, pre);
+                for (int q = 0; q < f; ++q) h[q] = gelu(pre[q]);
+                second_mlp(D, h, W2e, b2 + (size_t)e * d, o);
+                double dg = 0.0;
+                for (int m = 0; m < d; ++m) {
+                    const double dy = (double)dY[(size_t)t * d + m];
+                    dg += dy * o[m];
+                    dob[m] = g * dy;                                   // dl/do for this slot
+                }
+                dgate_out[(size_t)r * k + j] = dg;
+                for (int q = 0; q < f; ++q) {                          // rows 6 and 7
+                    const float* w = W2e + (size_t)q * d;
+                    double dh = 0.0;
+                    for (int m = 0; m < d; ++m) dh += dob[m] * (double)w[m];
+                    dpre[q] = dh * gelu_grad(pre[q]);
+                }
+                for (int i = 0; i < d; ++i) {                          // row 10
+                    const float* w = W1e + (size_t)i * f;
+                    double s = 0.0;
+                    for (int q = 0; q < f; ++q) s += dpre[q] * (double)w[q];
+                    dx[i] += s;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+// Backward, per-expert outputs for the listed experts, restricted to the
+// listed hidden units (cols == NULL: all f).  Each hidden unit n enters the
+// weight/bias gradients independently of the others, so the restriction is
+// the same formula on fewer n:
+//   db2 [ne][d]          = sum_a do_a                        (ESS,   row 4)
+//   dW2 [ne][nc][d]      = sum_a h_a[n] * do_a[:]            (ESTMM, row 5)
+//   db1 [ne][nc]         = sum_a dpre_a[n]                   (ESS,   row 8)
+//   dW1 [ne][d][nc]      = sum_a x_t[:] * dpre_a[n]          (ESTMM, row 9)
+// with a running over the expert's assignments in ascending flat id.
+int hexa_oracle_bwd_experts(int T, int d, int f, int E, int k, const float* x,
+                            const int32_t* topk_idx, const float* gate, const float* W1,
+                            const float* b1, const float* W2, const float* dY,
+                            const int32_t* experts, int n_experts, const int32_t* cols,
+                            int n_cols, double* dW1_out, double* db1_out, double* dW2_out,
+                            double* db2_out) {
+    Dims D{T, d, f, E, k};
+    if (bad_dims(D) || bad_routing(D, topk_idx)) return 1;
+    const int nc = cols ? n_cols : f;
+    for (int c = 0; c < nc; ++c)
+        if (cols && (cols[c] < 0 || cols[c] >= f)) return 1;
+    for (int s = 0; s < n_experts; ++s)
+        if (experts[s] < 0 || experts[s] >= E) return 1;
+    const size_t A = (size_t)T * k;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < n_experts; ++s) {
+        const int e = experts[s];
+        const float* W1e = W1 + (size_t)e * d * f;
+        const float* W2e = W2 + (size_t)e * f * d;
+        double* dW1 = dW1_out + (size_t)s * d * nc;
+        double* db1 = db1_out + (size_t)s * nc;
+        double* dW2 = dW2_out + (size_t)s * nc * d;
+        double* db2 = db2_out + (size_t)s * d;
+        for (size_t q = 0; q < (size_t)d * nc; ++q) dW1[q] = 0.0;
+        for (size_t q = 0; q < (size_t)nc * d; ++q) dW2[q] = 0.0;
+        for (int c = 0; c < nc; ++c) db1[c] = 0.0;
+        for (int m = 0; m < d; ++m) db2[m] = 0.0;
+        std::vector<double> dob(d), pre(nc), dpre(nc);
+        for (size_t a = 0; a < A; ++a) {
+            if (topk_idx[a] != e) continue;
+            const size_t t = a / k;
+            const double g = (double)gate[a];
+            const float* xt = x + t * d;
+            for (int m = 0; m < d; ++m) {
+                dob[m] = g * (double)dY[t * d + m];
+                db2[m] += dob[m];
+            }
+            for (int c = 0; c < nc; ++c) pre[c] = (double)b1[(size_t)e * f + (cols ? cols[c] : c)];
+            for (int i = 0; i < d; ++i) {
+                const double xi = (double)xt[i];
+                const float* w = W1e + (size_t)i * f;
+                if (cols) for (int c = 0; c < nc; ++c) pre[c] += xi * (double)w[cols[c]];
+                else      for (int c = 0; c < nc; ++c) pre[c] += xi * (double)w[c];
+            }
+            for (int c = 0; c < nc; ++c) {
+                const int n = cols ? cols[c] : c;
+                const double hn = gelu(pre[c]);
+                const float* w = W2e + (size_t)n * d;
+                double dh = 0.0;
+                for (int m = 0; m < d; ++m) {
+                    dW2[(size_t)c * d + m] += hn * dob[m];
+                    dh += dob[m] * (double)w[m];
+                }
+                dpre[c] = dh * gelu_grad(pre[c]);
+                db1[c] += dpre[c];
+            }
+            for (int i = 0; i < d; ++i) {
+                const double xi = (double)xt[i];
+                double* row = dW1 + (size_t)i * nc;
+                for (int c = 0; c < nc; ++c) row[c] += xi * dpre[c];
+            }
+        }
+    }
+    return 0;
+}
+
+// The scalar activation and its derivative, exposed so their constants can be
+// pinned on their own.
+double hexa_oracle_gelu(double u) { return gelu(u); }
+double hexa_oracle_gelu_grad(double u) { return gelu_grad(u); }
+
+}  // extern "C"
