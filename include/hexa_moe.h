@@ -1,0 +1,139 @@
+/* hexa_moe.h -- C ABI of the MI355X (gfx950) expert-specific MoE FFN layer.
+ *
+ * One top-k Mixture-of-Experts FFN layer, forward and backward, computed with
+ * routing-indexed ("expert-specific") operators: no capacity padding, no token
+ * dropping, all experts resident on one GPU.  (HEXA-MoE, arXiv 2411.01288:
+ * operators ESMM / ESS / ESTMM of Sec. 3.1; layer dataflow of App. B Table 5;
+ * re-index vector of Sec. 3.2 and App. B Alg. 1.)
+ *
+ * Notation: T tokens (the paper's N), d = d_model, f = d_ff, E experts, k = top-k,
+ * A = T*k assignments; flat assignment id a = t*k + j belongs to token t = a / k,
+ * expert e_a = topk_idx[a], gate g_a = gate[a].
+ *
+ * General rules
+ *   - Every pointer marked "dev" is device memory of the current HIP device;
+ *     the caller owns all of it.  No entry point allocates, frees or
+ *     synchronises; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns at once.
+ *   - All tensors are dense, row-major, without strides.
+ *   - Element type `shape.dtype` (HEXA_F32 or HEXA_BF16) applies to x, W1, b1,
+ *     W2, b2, y, dY, dx.  gate and dgate are float.  Weight and bias gradients
+ *     are float (the accumulation type).  Index tensors are int32.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - Errors are return codes; argument checks run on the host before any
+ *     launch, so a non-OK return means nothing was enqueued.
+ *   - HEXA_BF16 needs d % 64 == 0 and f % 64 == 0 (the paper's kernels likewise
+ *     assume feature sizes divisible by the tile, App. B); HEXA_F32 takes any
+ *     positive sizes.  E <= 1024.  A < 2^31 / max(d, f) is not required: row
+ *     offsets are 64-bit.
+ *   - Expert ids must satisfy 0 <= topk_idx < E (App. B Table 4).  An id outside
+ *     that range is not an error return (the host cannot see it): that
+ *     assignment is dropped from the index (inv = -1, offsets[E] < A), it
+ *     contributes nothing to y, and its dx/dgate contributions are zero.  A
+ *     caller that wants the check compares offsets[E] with A.
+ */
+#ifndef HEXA_MOE_H
+#define HEXA_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HEXA_API __attribute__((visibility("default")))
+
+typedef enum {
+    HEXA_OK = 0,
+    HEXA_ERR_NULL = 1,        /* a required pointer is NULL */
+    HEXA_ERR_SHAPE = 2,       /* a size is <= 0, A overflows int32, or E > 1024 */
+    HEXA_ERR_UNSUPPORTED = 3, /* dtype unknown, or bf16 with d or f not a multiple of 64 */
+    HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query */
+    HEXA_ERR_DEVICE = 5       /* a launch failed (hipGetLastError) */
+} hexa_status;
+
+typedef enum { HEXA_F32 = 0, HEXA_BF16 = 1 } hexa_dtype;
+
+typedef struct {
+    int32_t T, d_model, d_ff, E, k;
+    int32_t dtype; /* hexa_dtype */
+} hexa_moe_shape;
+
+/* The re-index structures (Sec. 3.2; App. B Alg. 1 and Table 4), all dev:
+ *   counts [E]    n_e = number of assignments routed to expert e
+ *   offsets[E+1]  exclusive prefix sum of counts; offsets[0] = 0, offsets[E] = A
+ *   perm   [A]    the re-index vector v without padding: flat assignment ids
+ *                 grouped by expert; inside a group in ascending id (the paper
+ *                 leaves that order to atomics; this library fixes it so the
+ *                 result is unique)
+ *   inv    [A]    inverse of perm: inv[perm[p]] = p
+ */
+typedef struct {
+    int32_t *counts, *offsets, *perm, *inv;
+} hexa_moe_idx;
+
+/* Bytes of device scratch hexa_moe_index needs (0 on an invalid shape). */
+HEXA_API size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape *shape);
+
+/* Bytes of device workspace shared by hexa_moe_fwd and hexa_moe_bwd (0 on an
+ * invalid shape).  It holds what the forward pass saves for the backward pass
+ * (pre-activations, activations and per-assignment expert outputs, in perm
+ * order) plus backward staging.  256-byte alignment of the base is required. */
+HEXA_API size_t hexa_moe_workspace_bytes(const hexa_moe_shape *shape);
+
+HEXA_API const char *hexa_moe_status_string(hexa_status s);
+
+/* Re-index build (App. B Alg. 1; Sec. 3.2 "Re-Index based Expert-Specific
+ * Operators"), for all k routing slots at once.
+ *   topk_idx [T,k] dev, in       routing choice R_j(x_t)
+ *   out      dev, out            counts, offsets, perm, inv as described above
+ *   scratch  dev, >= hexa_moe_index_scratch_bytes(); contents undefined after
+ * Integer work; the result is bit-exact and independent of scheduling. */
+HEXA_API hexa_status hexa_moe_index(const hexa_moe_shape *shape, const int32_t *topk_idx,
+                           hexa_moe_idx out, void *scratch, size_t scratch_bytes,
+                           void *stream);
+
+/* Forward (App. B Table 5 rows 1-3; ESMM of Sec. 3.1):
+ *   pre_a = x_t W1[e_a] + b1[e_a];  h_a = GELU_tanh(pre_a);  o_a = h_a W2[e_a] + b2[e_a]
+ *   y_t   = sum_j gate[t,j] * o_{t*k+j}
+ * (the paper's table sums the k slots unweighted; the gate factor is this
+ * library's reading, equal to the paper's for gate == 1).
+ *   x [T,d], W1 [E,d,f], b1 [E,f], W2 [E,f,d], b2 [E,d]   dev, in, shape.dtype
+ *   topk_idx [T,k] int32, gate [T,k] float                 dev, in
+ *   idx        as written by hexa_moe_index for this topk_idx  dev, in
+ *   y [T,d]    dev, out, shape.dtype
+ *   workspace  dev, >= hexa_moe_workspace_bytes(); afterwards holds the saved
+ *              state hexa_moe_bwd reads
+ * bf16: products in bf16 MFMA with fp32 accumulation; pre, h are stored
+ * rounded to bf16 (round-to-nearest-even). */
+HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, const int32_t *topk_idx,
+                         const float *gate, const void *W1, const void *b1, const void *W2,
+                         const void *b2, hexa_moe_idx idx, void *y, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/* Backward (App. B Table 5 rows 4-10; ESS and ESTMM of Sec. 3.1), with
+ * do_a = gate_a * dY_t:
+ *   db2[e] = sum_{a in e} do_a            dW2[e] = sum_{a in e} h_a^T do_a
+ *   dh_a = do_a W2[e_a]^T                 dpre_a = dh_a * GELU_tanh'(pre_a)
+ *   db1[e] = sum_{a in e} dpre_a          dW1[e] = sum_{a in e} x_t^T dpre_a
+ *   dx_t = sum_j dpre_{t*k+j} W1[e]^T     dgate[t,j] = <dY_t, o_{t*k+j}>
+ *   dY [T,d]                                    dev, in, shape.dtype
+ *   x, topk_idx, gate, W1, W2, idx              dev, in, as given to hexa_moe_fwd
+ *   workspace  dev, as left by hexa_moe_fwd for the same inputs (its saved part is
+ *              only read, so hexa_moe_bwd may be called again; staging is rewritten)
+ *   dx [T,d] shape.dtype; dW1 [E,d,f], db1 [E,f], dW2 [E,f,d], db2 [E,d] float
+ *                                               dev, out
+ *   dgate [T,k] float                           dev, out, or NULL to skip
+ * Experts with no tokens get exact zeros in dW1, db1, dW2, db2.  All sums run
+ * in a fixed order: results are reproducible run to run. */
+HEXA_API hexa_status hexa_moe_bwd(const hexa_moe_shape *shape, const void *dY, const void *x,
+                         const int32_t *topk_idx, const float *gate, const void *W1,
+                         const void *W2, hexa_moe_idx idx, void *workspace,
+                         size_t workspace_bytes, void *dx, float *dW1, float *db1, float *dW2,
+                         float *db2, float *dgate, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEXA_MOE_H */

@@ -1,0 +1,179 @@
+"""Thin Python binding of libhexa_moe (argument marshalling only).
+
+Same names as the C ABI in include/hexa_moe.h.  PyTorch supplies device memory
+and the current stream; every step of the layer runs in the library's kernels.
+Importing this module fails loudly when the library has not been built
+(`python -m paper_2411_01288_amd.build`): there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
+
+HEXA_F32, HEXA_BF16 = 0, 1
+EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
+           "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class Idx(ctypes.Structure):
+    _fields_ = [("counts", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
+                ("perm", ctypes.c_void_p), ("inv", ctypes.c_void_p)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2411_01288_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, S = ctypes.c_void_p, ctypes.c_size_t
+    lib.hexa_moe_index_scratch_bytes.restype = S
+    lib.hexa_moe_index_scratch_bytes.argtypes = [ctypes.POINTER(Shape)]
+    lib.hexa_moe_workspace_bytes.restype = S
+    lib.hexa_moe_workspace_bytes.argtypes = [ctypes.POINTER(Shape)]
+    lib.hexa_moe_status_string.restype = ctypes.c_char_p
+    lib.hexa_moe_status_string.argtypes = [ctypes.c_int]
+    lib.hexa_moe_index.restype = ctypes.c_int
+    lib.hexa_moe_index.argtypes = [ctypes.POINTER(Shape), P, Idx, P, S, P]
+    lib.hexa_moe_fwd.restype = ctypes.c_int
+    lib.hexa_moe_fwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, P, Idx, P, P, S, P]
+    lib.hexa_moe_bwd.restype = ctypes.c_int
+    lib.hexa_moe_bwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, Idx, P, S, P, P, P, P, P, P, P]
+    return lib
+
+
+lib = _load()
+
+
+class HexaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"hexa_moe status {code}: {lib.hexa_moe_status_string(code).decode()}")
+
+
+def _check(code: int):
+    if code != 0:
+        raise HexaError(code)
+
+
+def make_shape(T: int, d_model: int, d_ff: int, E: int, k: int, dtype) -> Shape:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: HEXA_F32, torch.bfloat16: HEXA_BF16}[dtype]
+    elif isinstance(dtype, str):
+        dtype = {"f32": HEXA_F32, "bf16": HEXA_BF16}[dtype]
+    return Shape(T, d_model, d_ff, E, k, dtype)
+
+
+def _tdt(shape: Shape):
+    return torch.float32 if shape.dtype == HEXA_F32 else torch.bfloat16
+
+
+def _ptr(t: Optional[torch.Tensor], dims, dtype, name: str):
+    """Device pointer of a dense tensor after checking placement, dtype and size on the host
+    (the kernels trust these sizes)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name}: need a contiguous device tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(dims):
+        raise ValueError(f"{name}: expected {tuple(dims)} {dtype}, got {tuple(t.shape)} {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def index_scratch_bytes(shape: Shape) -> int:
+    return lib.hexa_moe_index_scratch_bytes(ctypes.byref(shape))
+
+
+def workspace_bytes(shape: Shape) -> int:
+    return lib.hexa_moe_workspace_bytes(ctypes.byref(shape))
+
+
+def alloc_idx(shape: Shape, device) -> Dict[str, torch.Tensor]:
+    A = shape.T * shape.k
+    mk = lambda n: torch.empty(n, dtype=torch.int32, device=device)
+    return {"counts": mk(shape.E), "offsets": mk(shape.E + 1), "perm": mk(A), "inv": mk(A)}
+
+
+def _idx_struct(shape: Shape, idx: Dict[str, torch.Tensor]) -> Idx:
+    A = shape.T * shape.k
+    return Idx(_ptr(idx["counts"], (shape.E,), torch.int32, "counts"),
+               _ptr(idx["offsets"], (shape.E + 1,), torch.int32, "offsets"),
+               _ptr(idx["perm"], (A,), torch.int32, "perm"),
+               _ptr(idx["inv"], (A,), torch.int32, "inv"))
+
+
+def alloc_workspace(shape: Shape, device) -> torch.Tensor:
+    n = workspace_bytes(shape)
+    if n == 0:
+        _check(lib.hexa_moe_index(ctypes.byref(shape), None, Idx(), None, 0, None))  # raises the reason
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def hexa_moe_index(shape: Shape, topk_idx: torch.Tensor, idx: Optional[Dict[str, torch.Tensor]] = None,
+                   scratch: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    dev = topk_idx.device
+    if idx is None:
+        idx = alloc_idx(shape, dev)
+    if scratch is None:
+        scratch = torch.empty(max(index_scratch_bytes(shape), 256), dtype=torch.uint8, device=dev)
+    _check(lib.hexa_moe_index(ctypes.byref(shape),
+                              _ptr(topk_idx, (shape.T, shape.k), torch.int32, "topk_idx"),
+                              _idx_struct(shape, idx), ctypes.c_void_p(scratch.data_ptr()),
+                              scratch.numel(), _stream()))
+    return idx
+
+
+def hexa_moe_fwd(shape: Shape, x, topk_idx, gate, W1, b1, W2, b2, idx, workspace: torch.Tensor,
+                 y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T, d, f, E, k = shape.T, shape.d_model, shape.d_ff, shape.E, shape.k
+    dt = _tdt(shape)
+    if y is None:
+        y = torch.empty((T, d), dtype=dt, device=x.device)
+    _check(lib.hexa_moe_fwd(ctypes.byref(shape), _ptr(x, (T, d), dt, "x"),
+                            _ptr(topk_idx, (T, k), torch.int32, "topk_idx"),
+                            _ptr(gate, (T, k), torch.float32, "gate"),
+                            _ptr(W1, (E, d, f), dt, "W1"), _ptr(b1, (E, f), dt, "b1"),
+                            _ptr(W2, (E, f, d), dt, "W2"), _ptr(b2, (E, d), dt, "b2"),
+                            _idx_struct(shape, idx), _ptr(y, (T, d), dt, "y"),
+                            ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()))
+    return y
+
+
+def hexa_moe_bwd(shape: Shape, dY, x, topk_idx, gate, W1, W2, idx, workspace: torch.Tensor,
+                 want_dgate: bool = True, out: Optional[Dict[str, torch.Tensor]] = None
+                 ) -> Dict[str, torch.Tensor]:
+    T, d, f, E, k = shape.T, shape.d_model, shape.d_ff, shape.E, shape.k
+    dt = _tdt(shape)
+    dev = x.device
+    if out is None:
+        out = {"dx": torch.empty((T, d), dtype=dt, device=dev),
+               "dW1": torch.empty((E, d, f), dtype=torch.float32, device=dev),
+               "db1": torch.empty((E, f), dtype=torch.float32, device=dev),
+               "dW2": torch.empty((E, f, d), dtype=torch.float32, device=dev),
+               "db2": torch.empty((E, d), dtype=torch.float32, device=dev),
+               "dgate": torch.empty((T, k), dtype=torch.float32, device=dev) if want_dgate else None}
+    _check(lib.hexa_moe_bwd(ctypes.byref(shape), _ptr(dY, (T, d), dt, "dY"), _ptr(x, (T, d), dt, "x"),
+                            _ptr(topk_idx, (T, k), torch.int32, "topk_idx"),
+                            _ptr(gate, (T, k), torch.float32, "gate"),
+                            _ptr(W1, (E, d, f), dt, "W1"), _ptr(W2, (E, f, d), dt, "W2"),
+                            _idx_struct(shape, idx), ctypes.c_void_p(workspace.data_ptr()),
+                            workspace.numel(), _ptr(out["dx"], (T, d), dt, "dx"),
+                            _ptr(out["dW1"], (E, d, f), torch.float32, "dW1"),
+                            _ptr(out["db1"], (E, f), torch.float32, "db1"),
+                            _ptr(out["dW2"], (E, f, d), torch.float32, "dW2"),
+                            _ptr(out["db2"], (E, d), torch.float32, "db2"),
+                            _ptr(out.get("dgate"), (T, k), torch.float32, "dgate"), _stream()))
+    return out

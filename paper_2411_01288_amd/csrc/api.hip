@@ -1,0 +1,158 @@
+// C ABI of libhexa_moe: argument checks, workspace layout, and the launch sequence of the
+// layer (HEXA-MoE App. B Table 5).  See include/hexa_moe.h for the contract.
+#include "common.h"
+
+namespace {
+
+constexpr int kMaxExperts = 1024;
+
+hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
+    if (!s) return HEXA_ERR_NULL;
+    if (s->T <= 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return HEXA_ERR_SHAPE;
+    if (s->E > kMaxExperts) return HEXA_ERR_SHAPE;
+    if ((long long)s->T * s->k > 0x7fffffffLL) return HEXA_ERR_SHAPE;
+    if (s->dtype != HEXA_F32 && s->dtype != HEXA_BF16) return HEXA_ERR_UNSUPPORTED;
+    if (s->dtype == HEXA_BF16 && (s->d_model % 64 != 0 || s->d_ff % 64 != 0)) return HEXA_ERR_UNSUPPORTED;
+    D->T = s->T; D->d = s->d_model; D->f = s->d_ff; D->E = s->E; D->k = s->k; D->A = s->T * s->k;
+    return HEXA_OK;
+}
+
+// Carve the workspace.  base may be NULL (size query).
+MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
+    MoeWorkspace w{};
+    const size_t es = dtype == HEXA_BF16 ? 2 : 4;
+    const size_t A = (size_t)D.A, d = (size_t)D.d, f = (size_t)D.f;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void* p = base ? (void*)((uint8_t*)base + off) : nullptr;
+        off += align_up(bytes, 256);
+        return p;
+    };
+    w.pre = take(A * f * es);
+    w.h = take(A * f * es);
+    w.o = (float*)take(A * d * 4);
+    w.dout = take(A * d * es);
+    w.dpre = take(A * f * es);
+    w.dxp = (float*)take(A * d * 4);
+    w.colpart = (float*)take((A / 128 + D.E) * (d > f ? d : f) * 4);
+    if (dtype == HEXA_BF16) {
+        w.xg = take(A * d * es);
+        w.kpart_slots = wgrad_max_slots(D);
+        w.kpart = (float*)take(w.kpart_slots * d * f * 4);
+    }
+    w.total_bytes = off;
+    return w;
+}
+
+bool any_null(std::initializer_list<const void*> ps) {
+    for (const void* p : ps)
+        if (!p) return true;
+    return false;
+}
+
+hexa_status dev(hipError_t e) { return e == hipSuccess ? HEXA_OK : HEXA_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape* shape) {
+    MoeDims D;
+    if (check_shape(shape, &D) != HEXA_OK) return 0;
+    return index_scratch_bytes(D);
+}
+
+size_t hexa_moe_workspace_bytes(const hexa_moe_shape* shape) {
+    MoeDims D;
+    if (check_shape(shape, &D) != HEXA_OK) return 0;
+    return layout(D, shape->dtype, nullptr).total_bytes;
+}
+
+const char* hexa_moe_status_string(hexa_status s) {
+    switch (s) {
+        case HEXA_OK: return "ok";
+        case HEXA_ERR_NULL: return "a required pointer is NULL";
+        case HEXA_ERR_SHAPE: return "invalid shape";
+        case HEXA_ERR_UNSUPPORTED: return "unsupported dtype or feature size";
+        case HEXA_ERR_WORKSPACE: return "scratch or workspace too small";
+        case HEXA_ERR_DEVICE: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+hexa_status hexa_moe_index(const hexa_moe_shape* shape, const int32_t* topk_idx, hexa_moe_idx out,
+                           void* scratch, size_t scratch_bytes, void* stream) {
+    MoeDims D;
+    const hexa_status s = check_shape(shape, &D);
+    if (s != HEXA_OK) return s;
+    if (any_null({topk_idx, out.counts, out.offsets, out.perm, out.inv, scratch})) return HEXA_ERR_NULL;
+    if (scratch_bytes < index_scratch_bytes(D)) return HEXA_ERR_WORKSPACE;
+    return dev(launch_index(D, topk_idx, out, scratch, (hipStream_t)stream));
+}
+
+hexa_status hexa_moe_fwd(const hexa_moe_shape* shape, const void* x, const int32_t* topk_idx,
+                         const float* gate, const void* W1, const void* b1, const void* W2,
+                         const void* b2, hexa_moe_idx idx, void* y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    MoeDims D;
+    const hexa_status s = check_shape(shape, &D);
+    if (s != HEXA_OK) return s;
+    if (any_null({x, topk_idx, gate, W1, b1, W2, b2, idx.counts, idx.offsets, idx.perm, idx.inv, y,
+                  workspace}))
+        return HEXA_ERR_NULL;
+    const MoeWorkspace ws = layout(D, shape->dtype, workspace);
+    if (workspace_bytes < ws.total_bytes) return HEXA_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (shape->dtype == HEXA_F32) {
+        e = launch_f32_fwd(D, (const float*)x, (const float*)W1, (const float*)b1, (const float*)W2,
+                           (const float*)b2, idx, ws, st);
+        if (e == hipSuccess) e = launch_combine_y<float>(D, ws.o, idx.inv, gate, (float*)y, st);
+    } else {
+        e = launch_bf16_fwd(D, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)b1,
+                            (const bf16_t*)W2, (const bf16_t*)b2, idx, ws, st);
+        if (e == hipSuccess) e = launch_combine_y<bf16_t>(D, ws.o, idx.inv, gate, (bf16_t*)y, st);
+    }
+    return dev(e);
+}
+
+hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void* x,
+                         const int32_t* topk_idx, const float* gate, const void* W1, const void* W2,
+                         hexa_moe_idx idx, void* workspace, size_t workspace_bytes, void* dx,
+                         float* dW1, float* db1, float* dW2, float* db2, float* dgate, void* stream) {
+    MoeDims D;
+    const hexa_status s = check_shape(shape, &D);
+    if (s != HEXA_OK) return s;
+    if (any_null({dY, x, topk_idx, gate, W1, W2, idx.counts, idx.offsets, idx.perm, idx.inv, workspace,
+                  dx, dW1, db1, dW2, db2}))
+        return HEXA_ERR_NULL;
+    const MoeWorkspace ws = layout(D, shape->dtype, workspace);
+    if (workspace_bytes < ws.total_bytes) return HEXA_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (shape->dtype == HEXA_F32) {
+        e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, ws.o, idx.perm,
+                                       idx.offsets, gate, (float*)ws.dout, dgate, st);
+        if (e == hipSuccess)
+            e = launch_segment_colsum<float>(D, (const float*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
+        if (e == hipSuccess)
+            e = launch_f32_bwd(D, (const float*)x, (const float*)W1, (const float*)W2, idx, ws, dW1, dW2, st);
+        if (e == hipSuccess)
+            e = launch_segment_colsum<float>(D, (const float*)ws.dpre, D.f, idx.offsets, ws.colpart, db1, st);
+        if (e == hipSuccess) e = launch_combine_dx<float>(D, ws.dxp, idx.inv, (float*)dx, st);
+    } else {
+        e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, ws.o,
+                                        idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, st);
+        if (e == hipSuccess)
+            e = launch_segment_colsum<bf16_t>(D, (const bf16_t*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
+        if (e == hipSuccess)
+            e = launch_bf16_bwd(D, (const bf16_t*)ws.xg, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
+                                dW1, dW2, st);
+        if (e == hipSuccess)
+            e = launch_segment_colsum<bf16_t>(D, (const bf16_t*)ws.dpre, D.f, idx.offsets, ws.colpart, db1, st);
+        if (e == hipSuccess) e = launch_combine_dx<bf16_t>(D, ws.dxp, idx.inv, (bf16_t*)dx, st);
+    }
+    return dev(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// Shared device helpers and the internal launcher interface of libhexa_moe.
+// gfx950 (CDNA4) only: 64-wide wavefronts, bf16 MFMA, 160 KB LDS per CU.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/hexa_moe.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// round-to-nearest-even; gfx950 lowers this cast to v_cvt_pk_bf16_f32
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    __device__ static float ld(const float* p) { return *p; }
+    __device__ static void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    __device__ static float ld(const bf16_t* p) { return bf2f(*p); }
+    __device__ static void st(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// GELU, tanh form (the activation F between the two MLPs; App. B Table 5 rows 2, 7).
+#define HEXA_GELU_C 0.7978845608028654f
+#define HEXA_GELU_A 0.044715f
+
+// A segment tile: `rows` (<= BM) consecutive rows of perm order that all belong
+// to expert `e`, starting at perm position `row0`.
+struct SegTile { int e, row0, rows; };
+
+// Number of BM-row tiles over all expert segments (each segment tiled on its own,
+// so no tile straddles two experts and none is padded to a capacity).
+__device__ __forceinline__ int seg_tiles_total(const int32_t* __restrict__ offsets, int E, int BM) {
+    int total = 0;
+    for (int e = 0; e < E; ++e) total += ceil_div(offsets[e + 1] - offsets[e], BM);
+    return total;
+}
+
+// Map tile number `tile` (0-based over all segments, expert-major) to its segment tile.
+// Returns e = -1 when `tile` is past the last one.
+__device__ __forceinline__ SegTile seg_tile_find(const int32_t* __restrict__ offsets, int E, int BM,
+                                                 int tile) {
+    SegTile s{-1, 0, 0};
+    int acc = 0;
+    for (int e = 0; e < E; ++e) {
+        const int b = offsets[e], n = offsets[e + 1] - b;
+        const int nt = ceil_div(n, BM);
+        if (tile < acc + nt) {
+            const int r0 = (tile - acc) * BM;
+            s.e = e; s.row0 = b + r0; s.rows = min(BM, n - r0);
+            return s;
+        }
+        acc += nt;
+    }
+    return s;
+}
+
+// ---- internal launchers (one per translation unit), all asynchronous on `st` ----
+struct MoeDims { int T, d, f, E, k, A; };
+
+// saved + staging regions inside the caller's workspace (device pointers)
+struct MoeWorkspace {
+    void* pre;      // [A,f] elem   pre-activations, perm order        (saved by fwd)
+    void* h;        // [A,f] elem   activations, perm order            (saved by fwd)
+    float* o;       // [A,d] f32    per-assignment expert outputs      (saved by fwd)
+    void* dout;     // [A,d] elem   gate * dY gathered to perm order   (bwd staging)
+    void* dpre;     // [A,f] elem                                       (bwd staging)
+    float* dxp;     // [A,d] f32    per-assignment input gradients     (bwd staging)
+    void* xg;       // [A,d] elem   x gathered to perm order (bf16 path)(bwd staging)
+    float* colpart; // [A/128+E, max(d,f)] f32 partial column sums     (bwd staging)
+    float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
+    size_t kpart_slots;
+    size_t total_bytes;
+};
+
+int wgrad_chunk_len(const MoeDims& D);          // tokens per split-K chunk (host policy)
+size_t wgrad_max_slots(const MoeDims& D);
+
+hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx out, void* scratch,
+                        hipStream_t st);
+size_t index_scratch_bytes(const MoeDims& D);
+
+template <typename T>
+hipError_t launch_combine_y(const MoeDims& D, const float* o, const int32_t* inv, const float* gate,
+                            T* y, hipStream_t st);
+// dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, and (when xg != NULL) xg_p = x_t, for a = perm[p]
+template <typename T>
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const float* o,
+                               const int32_t* perm, const int32_t* offsets, const float* gate,
+                               T* dout, float* dgate, hipStream_t st);
+template <typename T>
+hipError_t launch_combine_dx(const MoeDims& D, const float* dxp, const int32_t* inv, T* dx,
+                             hipStream_t st);
+// ESS: out[e][c] = sum over the expert's rows of src[p][c]; src is [A, ncols] in perm order
+template <typename T>
+hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, const int32_t* offsets,
+                                 float* partial, float* out, hipStream_t st);
+
+// fp32 reference-precision path (plain FMA tiles)
+hipError_t launch_f32_fwd(const MoeDims& D, const float* x, const float* W1, const float* b1,
+                          const float* W2, const float* b2, const hexa_moe_idx& idx,
+                          const MoeWorkspace& ws, hipStream_t st);
+hipError_t launch_f32_bwd(const MoeDims& D, const float* x, const float* W1, const float* W2,
+                          const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
+                          hipStream_t st);
+
+// bf16 MFMA path
+hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* b1,
+                           const bf16_t* W2, const bf16_t* b2, const hexa_moe_idx& idx,
+                           const MoeWorkspace& ws, hipStream_t st);
+hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* W2,
+                           const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
+                           hipStream_t st);

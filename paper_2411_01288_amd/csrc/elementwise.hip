@@ -1,0 +1,256 @@
+// Bandwidth-bound steps around the contractions:
+//   combine_y      y_t  = sum_j gate[t,j] * o[inv[t*k+j]]          (top-k sum of App. B Table 5 row 3,
+//                                                                    done as a gather in fixed slot order
+//                                                                    instead of the paper's atomicAdd)
+//   bwd_prologue   do_p = gate_a * dY_t  (a = perm[p]) ; dgate_a = <dY_t, o_p>
+//   combine_dx     dx_t = sum_j dxp[inv[t*k+j]]                     (Table 5 row 10, sum over the k slots)
+//   segment_colsum ESS (Sec. 3.1 item 2; App. B Alg. 3): per-expert column sums of a perm-ordered
+//                  matrix, in two deterministic stages so a long segment is spread over the chip.
+#include "common.h"
+
+namespace {
+
+template <typename T> struct Vec;   // 16-byte vector access of 4 floats or 8 bf16
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float* p, float (&v)[4]) {
+        const float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    __device__ static void store(float* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const bf16_t* p, float (&v)[8]) {
+        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static void store(bf16_t* p, const float (&v)[8]) {
+        uint4 q;
+        q.x = pack_bf2(v[0], v[1]); q.y = pack_bf2(v[2], v[3]);
+        q.z = pack_bf2(v[4], v[5]); q.w = pack_bf2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = q;
+    }
+};
+
+// One thread per VN consecutive columns of one token.  d % VN == 0.
+template <typename T>
+__global__ __launch_bounds__(256) void combine_rows(int T_, int d, int k,
+                                                    const float* __restrict__ src,
+                                                    const int32_t* __restrict__ inv,
+                                                    const float* __restrict__ gate,  // NULL: plain sum
+                                                    T* __restrict__ dst) {
+    constexpr int VN = Vec<T>::N;
+    const int per_row = d / VN;
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= (long long)T_ * per_row) return;
+    const int t = (int)(gid / per_row);
+    const int c = (int)(gid % per_row) * VN;
+    float acc[VN];
+#pragma unroll
+    for (int i = 0; i < VN; ++i) acc[i] = 0.f;
+    for (int j = 0; j < k; ++j) {
+        const int p = inv[(size_t)t * k + j];
+        if (p < 0) continue;  // dropped assignment
+        const float g = gate ? gate[(size_t)t * k + j] : 1.f;
+        const float* s = src + (size_t)p * d + c;
+#pragma unroll
+        for (int q = 0; q < VN; q += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(s + q);
+            acc[q] += g * v.x; acc[q + 1] += g * v.y; acc[q + 2] += g * v.z; acc[q + 3] += g * v.w;
+        }
+    }
+    Vec<T>::store(dst + (size_t)t * d + c, acc);
+}
+
+// Tail columns when d is not a multiple of the vector width (fp32 path with odd sizes).
+template <typename T>
+__global__ __launch_bounds__(256) void combine_rows_scalar(int T_, int d, int k,
+                                                           const float* __restrict__ src,
+                                                           const int32_t* __restrict__ inv,
+                                                           const float* __restrict__ gate,
+                                                           T* __restrict__ dst) {
+    const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= (long long)T_ * d) return;
+    const int t = (int)(gid / d), c = (int)(gid % d);
+    float acc = 0.f;
+    for (int j = 0; j < k; ++j) {
+        const int p = inv[(size_t)t * k + j];
+        if (p < 0) continue;
+        const float g = gate ? gate[(size_t)t * k + j] : 1.f;
+        acc += g * src[(size_t)p * d + c];
+    }
+    Elem<T>::st(dst + (size_t)t * d + c, acc);
+}
+
+// One wavefront per perm row p.
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T* __restrict__ dY,
+                                                    const T* __restrict__ x, T* __restrict__ xg,
+                                                    const float* __restrict__ o,
+                                                    const int32_t* __restrict__ perm,
+                                                    const int32_t* __restrict__ offsets, int E,
+                                                    const float* __restrict__ gate,
+                                                    T* __restrict__ dout, float* __restrict__ dgate) {
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= A) return;
+    const int n_valid = offsets[E];
+    if (p >= n_valid) {  // rows past the last segment exist only when ids were dropped
+        for (int c = lane; c < d; c += 64) {
+            Elem<T>::st(dout + (size_t)p * d + c, 0.f);
+            if (xg) Elem<T>::st(xg + (size_t)p * d + c, 0.f);
+        }
+        return;
+    }
+    const int a = perm[p];
+    const int t = a / k;
+    const float g = gate[a];
+    const T* src = dY + (size_t)t * d;
+    const float* orow = o + (size_t)p * d;
+    T* dst = dout + (size_t)p * d;
+    float dot = 0.f;
+    constexpr int VN = Vec<T>::N;
+    if (d % VN == 0) {
+        for (int c = lane * VN; c < d; c += 64 * VN) {
+            float v[VN], w[VN];
+            Vec<T>::load(src + c, v);
+#pragma unroll
+            for (int q = 0; q < VN; q += 4) {
+                const float4 ov = *reinterpret_cast<const float4*>(orow + c + q);
+                dot += v[q] * ov.x + v[q + 1] * ov.y + v[q + 2] * ov.z + v[q + 3] * ov.w;
+            }
+#pragma unroll
+            for (int q = 0; q < VN; ++q) w[q] = g * v[q];
+            Vec<T>::store(dst + c, w);
+            if (xg)
+                *reinterpret_cast<uint4*>(xg + (size_t)p * d + c) =
+                    *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
+        }
+    } else {
+        for (int c = lane; c < d; c += 64) {
+            const float v = Elem<T>::ld(src + c);
+            dot += v * orow[c];
+            Elem<T>::st(dst + c, g * v);
+            if (xg) xg[(size_t)p * d + c] = x[(size_t)t * d + c];
+        }
+    }
+    if (dgate) {
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) dot += __shfl_xor(dot, s);
+        if (lane == 0) dgate[a] = dot;
+    }
+}
+
+__global__ void fill_zero_f32(float* p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// Stage 1: one workgroup per (128-row segment tile, 256-column block): each thread owns one column
+// pair-free scalar column and walks the rows in order -> partial[tile][col].
+constexpr int kColsumRows = 128;
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ src, int ncols, int E,
+                                                     const int32_t* __restrict__ offsets,
+                                                     float* __restrict__ partial) {
+    const SegTile s = seg_tile_find(offsets, E, kColsumRows, blockIdx.x);
+    if (s.e < 0) return;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= ncols) return;
+    float acc = 0.f;
+    const T* p = src + (size_t)s.row0 * ncols + c;
+    for (int r = 0; r < s.rows; ++r) acc += Elem<T>::ld(p + (size_t)r * ncols);
+    partial[(size_t)blockIdx.x * ncols + c] = acc;
+}
+
+// Stage 2: out[e][c] = sum of the expert's tile partials in tile order (exact 0 for an empty expert).
+__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int ncols,
+                                                     int E, const int32_t* __restrict__ offsets,
+                                                     float* __restrict__ out) {
+    const int e = blockIdx.x;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= ncols) return;
+    int first = 0;
+    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], kColsumRows);
+    const int nt = ceil_div(offsets[e + 1] - offsets[e], kColsumRows);
+    float acc = 0.f;
+    for (int i = 0; i < nt; ++i) acc += partial[(size_t)(first + i) * ncols + c];
+    out[(size_t)e * ncols + c] = acc;
+}
+
+template <typename T>
+hipError_t combine_impl(int T_, int d, int k, const float* src, const int32_t* inv,
+                        const float* gate, T* dst, hipStream_t st) {
+    constexpr int VN = Vec<T>::N;
+    if (d % VN == 0) {
+        const long long n = (long long)T_ * (d / VN);
+        hipLaunchKernelGGL(combine_rows<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, T_,
+                           d, k, src, inv, gate, dst);
+    } else {
+        const long long n = (long long)T_ * d;
+        hipLaunchKernelGGL(combine_rows_scalar<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                           st, T_, d, k, src, inv, gate, dst);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+template <typename T>
+hipError_t launch_combine_y(const MoeDims& D, const float* o, const int32_t* inv, const float* gate,
+                            T* y, hipStream_t st) {
+    return combine_impl<T>(D.T, D.d, D.k, o, inv, gate, y, st);
+}
+
+template <typename T>
+hipError_t launch_combine_dx(const MoeDims& D, const float* dxp, const int32_t* inv, T* dx,
+                             hipStream_t st) {
+    return combine_impl<T>(D.T, D.d, D.k, dxp, inv, nullptr, dx, st);
+}
+
+template <typename T>
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const float* o,
+                               const int32_t* perm, const int32_t* offsets, const float* gate,
+                               T* dout, float* dgate, hipStream_t st) {
+    if (dgate) {  // dropped assignments keep a defined (zero) gate gradient
+        const size_t n = (size_t)D.A;
+        hipLaunchKernelGGL(fill_zero_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dgate, n);
+    }
+    hipLaunchKernelGGL(bwd_prologue<T>, dim3(ceil_div(D.A, 4)), dim3(256), 0, st, D.A, D.d, D.k, dY,
+                       x, xg, o, perm, offsets, D.E, gate, dout, dgate);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, const int32_t* offsets,
+                                 float* partial, float* out, hipStream_t st) {
+    const int max_tiles = D.A / kColsumRows + D.E;
+    const int cb = ceil_div(ncols, 256);
+    hipLaunchKernelGGL(colsum_stage1<T>, dim3(max_tiles, cb), dim3(256), 0, st, src, ncols, D.E,
+                       offsets, partial);
+    hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, offsets,
+                       out);
+    return hipGetLastError();
+}
+
+#define INSTANTIATE(T)                                                                              \
+    template hipError_t launch_combine_y<T>(const MoeDims&, const float*, const int32_t*,          \
+                                            const float*, T*, hipStream_t);                        \
+    template hipError_t launch_combine_dx<T>(const MoeDims&, const float*, const int32_t*, T*,     \
+                                             hipStream_t);                                         \
+    template hipError_t launch_bwd_prologue<T>(const MoeDims&, const T*, const T*, T*,             \
+                                               const float*, const int32_t*, const int32_t*,       \
+                                               const float*, T*, float*, hipStream_t);             \
+    template hipError_t launch_segment_colsum<T>(const MoeDims&, const T*, int, const int32_t*,    \
+                                                 float*, float*, hipStream_t);
+INSTANTIATE(float)
+INSTANTIATE(bf16_t)

@@ -1,0 +1,181 @@
+// Re-index build (HEXA-MoE Sec. 3.2; App. B Alg. 1), redesigned for CDNA4.
+//
+// The paper scatters token ids with one global atomicAdd per token, which makes
+// the order inside an expert's segment depend on scheduling.  Here the result is
+// the unique stable counting sort of the flat assignment ids, built without any
+// order-dependent atomic:
+//   1. index_count   each wavefront owns a contiguous run of ids and histograms
+//                    it in LDS (integer adds commute, so the counts are exact);
+//   2. index_scan    one workgroup turns the [chunk][expert] histogram into
+//                    counts, offsets and, per chunk and expert, the first output
+//                    position (expert-major, chunk-minor exclusive scan);
+//   3. index_scatter each wavefront re-reads its run 64 ids at a time; the rank
+//                    of an id among equal experts in its row comes from
+//                    ballot + popcount of the lower lanes, rows are chained
+//                    through a per-wave LDS cursor.
+// Segments carry no padding: tiles are cut per segment by the consumers.
+#include "common.h"
+
+namespace {
+
+constexpr int kWavesPerWg = 4;
+constexpr int kMaxChunks = 1024;
+
+struct IndexPlan { int rows_per_wave, nchunks; };
+
+IndexPlan plan_for(int A) {
+    IndexPlan p;
+    p.rows_per_wave = (A + 64 * kMaxChunks - 1) / (64 * kMaxChunks);
+    if (p.rows_per_wave < 1) p.rows_per_wave = 1;
+    p.nchunks = (A + 64 * p.rows_per_wave - 1) / (64 * p.rows_per_wave);
+    return p;
+}
+
+__global__ __launch_bounds__(256) void index_count(const int32_t* __restrict__ idx, int A, int E,
+                                                   int R, int nchunks, int32_t* __restrict__ hist) {
+    extern __shared__ int32_t lh[];  // [4][E]
+    for (int i = threadIdx.x; i < kWavesPerWg * E; i += 256) lh[i] = 0;
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * kWavesPerWg + wave;
+    if (chunk < nchunks) {
+        const int a0 = chunk * 64 * R;
+        for (int r = 0; r < R; ++r) {
+            const int a = a0 + r * 64 + lane;
+            if (a < A) {
+                const int e = idx[a];
+                if ((unsigned)e < (unsigned)E) atomicAdd(&lh[wave * E + e], 1);
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kWavesPerWg * E; i += 256) {
+        const int c = blockIdx.x * kWavesPerWg + i / E;
+        if (c < nchunks) hist[(size_t)c * E + i % E] = lh[i];
+    }
+}
+
+// hist[c][e] (counts) -> hist[c][e] (first output position of chunk c's ids of expert e)
+__global__ __launch_bounds__(1024) void index_scan(int32_t* __restrict__ hist, int E, int nchunks,
+                                                   int32_t* __restrict__ counts,
+                                                   int32_t* __restrict__ offsets) {
+    __shared__ int32_t gs[1024];   // [G][E] group sums, then exclusive group bases
+    __shared__ int32_t cnt[1024];  // counts, then offsets
+    const int G = max(1, 1024 / E);
+    const int cpg = ceil_div(nchunks, G);
+    const int t = threadIdx.x;
+    const int e = t % E, g = t / E;
+    const bool active = g < G;
+    const int c0 = g * cpg, c1 = min(nchunks, c0 + cpg);
+    int s = 0;
+    if (active)
+        for (int c = c0; c < c1; ++c) s += hist[(size_t)c * E + e];
+    if (active) gs[g * E + e] = s;
+    __syncthreads();
+    int base = 0;
+    if (active) {
+        for (int q = 0; q < g; ++q) base += gs[q * E + e];
+        if (g == 0) {
+            int tot = 0;
+            for (int q = 0; q < G; ++q) tot += gs[q * E + e];
+            cnt[e] = tot;
+            counts[e] = tot;
+        }
+    }
+    __syncthreads();
+    int off = 0, mine = 0;
+    if (t < E) {
+        for (int q = 0; q < t; ++q) off += cnt[q];
+        mine = cnt[t];
+    }
+    __syncthreads();
+    if (t < E) {
+        cnt[t] = off;
+        offsets[t] = off;
+        if (t == E - 1) offsets[E] = off + mine;
+    }
+    __syncthreads();
+    if (active) {
+        int run = cnt[e] + base;
+        for (int c = c0; c < c1; ++c) {
+            const size_t i = (size_t)c * E + e;
+            const int v = hist[i];
+            hist[i] = run;
+            run += v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void index_scatter(const int32_t* __restrict__ idx, int A, int E,
+                                                     int R, int nchunks,
+                                                     const int32_t* __restrict__ hist,
+                                                     const int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ perm,
+                                                     int32_t* __restrict__ inv) {
+    extern __shared__ int32_t lraw[];  // [4][E] cursors
+    volatile int32_t* lb = lraw;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * kWavesPerWg + wave;
+    for (int i = threadIdx.x; i < kWavesPerWg * E; i += 256) {
+        const int c = blockIdx.x * kWavesPerWg + i / E;
+        lraw[i] = c < nchunks ? hist[(size_t)c * E + i % E] : 0;
+    }
+    __syncthreads();
+    if (chunk >= nchunks) return;
+    const int n_valid = offsets[E];
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const int a0 = chunk * 64 * R;
+    for (int r = 0; r < R; ++r) {
+        const int a = a0 + r * 64 + lane;
+        int e = -1;
+        if (a < A) e = idx[a];
+        const bool valid = (a < A) && ((unsigned)e < (unsigned)E);
+        uint64_t remaining = __ballot(valid);
+        int rank = 0, cnt = 0;
+        while (remaining) {  // uniform: one trip per distinct expert in this row
+            const int leader = __ffsll((long long)remaining) - 1;
+            const int e0 = __shfl(e, leader);
+            const uint64_t m = __ballot(valid && e == e0);
+            if (valid && e == e0) {
+                rank = __popcll(m & lt_mask);
+                cnt = __popcll(m);
+            }
+            remaining &= ~m;
+        }
+        int b = 0;
+        if (valid) b = lb[wave * E + e];
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            const int pos = b + rank;
+            perm[pos] = a;
+            inv[a] = pos;
+            if (rank == cnt - 1) lb[wave * E + e] = b + cnt;
+        } else if (a < A) {
+            inv[a] = -1;  // dropped: expert id outside [0, E)
+        }
+        if (a < A && a >= n_valid) perm[a] = -1;  // tail left empty by dropped ids
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+}  // namespace
+
+size_t index_scratch_bytes(const MoeDims& D) {
+    const IndexPlan p = plan_for(D.A);
+    return align_up((size_t)p.nchunks * D.E * sizeof(int32_t), 256);
+}
+
+hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx out, void* scratch,
+                        hipStream_t st) {
+    const IndexPlan p = plan_for(D.A);
+    int32_t* hist = (int32_t*)scratch;
+    const int nwg = ceil_div(p.nchunks, kWavesPerWg);
+    const size_t lds = (size_t)kWavesPerWg * D.E * sizeof(int32_t);
+    hipLaunchKernelGGL(index_count, dim3(nwg), dim3(256), lds, st, topk_idx, D.A, D.E,
+                       p.rows_per_wave, p.nchunks, hist);
+    hipLaunchKernelGGL(index_scan, dim3(1), dim3(1024), 0, st, hist, D.E, p.nchunks, out.counts,
+                       out.offsets);
+    hipLaunchKernelGGL(index_scatter, dim3(nwg), dim3(256), lds, st, topk_idx, D.A, D.E,
+                       p.rows_per_wave, p.nchunks, hist, out.offsets, out.perm, out.inv);
+    return hipGetLastError();
+}

@@ -1,0 +1,39 @@
+"""Helpers shared by the GPU parity tests: run the HIP library through its binding and
+bring results to the host.  Nothing here computes any part of the layer."""
+import numpy as np
+import torch
+
+
+def run_hip_layer(w, data, want_dgate=True):
+    """data: dict of device tensors from workloads.generate.  Returns (idx, y, grads) on device."""
+    from paper_2411_01288_amd import binding as B
+    shape = B.make_shape(w.T, w.d_model, w.d_ff, w.E, w.k, w.dtype)
+    dev = data["x"].device
+    idx = B.hexa_moe_index(shape, data["topk_idx"])
+    ws = B.alloc_workspace(shape, dev)
+    y = B.hexa_moe_fwd(shape, data["x"], data["topk_idx"], data["gate"], data["W1"], data["b1"],
+                       data["W2"], data["b2"], idx, ws)
+    g = B.hexa_moe_bwd(shape, data["dY"], data["x"], data["topk_idx"], data["gate"], data["W1"],
+                       data["W2"], idx, ws, want_dgate=want_dgate)
+    torch.cuda.synchronize()
+    return idx, y, g
+
+
+def host32(t):
+    return t.detach().to("cpu").float().numpy()
+
+
+def host_inputs(data):
+    c = {k: host32(v) for k, v in data.items() if k != "topk_idx"}
+    c["topk_idx"] = data["topk_idx"].cpu().numpy()
+    return c
+
+
+def nrm_err(got, ref):
+    """max |got - ref| / max |ref|  (the max-abs normalised error of the tolerance statement)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
