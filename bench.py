@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark: one MoE FFN layer, index build + forward + backward, on one MI355X.
+
+A step is one pass of the whole hot path (hexa_moe_index, hexa_moe_fwd, hexa_moe_bwd) over one
+synthetic batch that is already resident in HBM.  Prints ONE JSON line.
+
+  value     useful TFLOP/s = 12 * T*k * d_model * d_ff / step time   (2 GEMMs forward, 4 backward)
+  roofline  the slowest kernel of the step (always one of the six bf16 MFMA contractions):
+            its 2*A*d*f FLOP over its average launch duration, measured with HIP events that the
+            library records on the launch stream, against the 2.5 PFLOP/s dense bf16 MFMA peak
+  cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0
+METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
+GEMM_LABELS = ("fc1", "fc2", "dgrad2", "dgrad1", "wgrad2", "wgrad1")
+
+
+def cpu_baseline(w, data, sample_tokens=64, col_frac=16):
+    """Oracle (fp64 loop nest) timed on the first `sample_tokens` tokens of the batch with all
+    experts resident; the per-expert gradients on f/col_frac of the hidden units (each hidden
+    unit is an independent, equal share of that work).  Returns useful TFLOP/s per the same
+    12*d*f FLOP per assignment."""
+    from oracle import hexa_oracle as O
+    O.build()
+    S = min(sample_tokens, w.T)
+    h = lambda t: t.detach().to("cpu").float().numpy()
+    x, dY, gate = h(data["x"][:S]), h(data["dY"][:S]), h(data["gate"][:S])
+    idx = data["topk_idx"][:S].cpu().numpy()
+    W1, b1, W2, b2 = h(data["W1"]), h(data["b1"]), h(data["W2"]), h(data["b2"])
+    ncols = max(1, w.d_ff // col_frac)
+    cols = np.arange(ncols, dtype=np.int32)
+    t0 = time.perf_counter()
+    O.fwd(x, idx, gate, W1, b1, W2, b2)
+    t1 = time.perf_counter()
+    O.bwd_tokens(x, idx, gate, W1, b1, W2, b2, dY)
+    t2 = time.perf_counter()
+    O.bwd_experts(x, idx, gate, W1, b1, W2, dY, cols=cols)
+    t3 = time.perf_counter()
+    per_assign = ((t1 - t0) + (t2 - t1) + (t3 - t2) * (w.d_ff / ncols)) / (S * w.k)
+    tflops = 12.0 * w.d_model * w.d_ff / per_assign / 1e12
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "sample": (f"first {S} tokens ({S * w.k} assignments) of the same batch, all {w.E} experts "
+                   f"resident; fwd {t1 - t0:.2f}s + dx/dgate {t2 - t1:.2f}s + weight/bias grads on "
+                   f"{ncols}/{w.d_ff} hidden units {t3 - t2:.2f}s (scaled x{w.d_ff // ncols}); "
+                   f"rate = 12*d*f / time per assignment"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C5")
+    ap.add_argument("--routing", default=None, help="override the routing recipe (zipf, forced, ...)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (all experts resident, no collectives); "
+                 "run with --gpus 1")
+
+    from paper_2411_01288_amd import binding as B
+    from paper_2411_01288_amd.workloads import generate, workload
+
+    ov = {"routing": args.routing} if args.routing else {}
+    w = workload(args.workload, **ov)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    data = generate(w, dev)
+    shape = B.make_shape(w.T, w.d_model, w.d_ff, w.E, w.k, w.dtype)
+    idx = B.alloc_idx(shape, dev)
+    iscratch = torch.empty(max(B.index_scratch_bytes(shape), 256), dtype=torch.uint8, device=dev)
+    ws = B.alloc_workspace(shape, dev)
+    y = torch.empty((w.T, w.d_model), dtype=data["x"].dtype, device=dev)
+    grads = None
+
+    def step():
+        nonlocal grads
+        B.hexa_moe_index(shape, data["topk_idx"], idx, iscratch)
+        B.hexa_moe_fwd(shape, data["x"], data["topk_idx"], data["gate"], data["W1"], data["b1"],
+                       data["W2"], data["b2"], idx, ws, y)
+        grads = B.hexa_moe_bwd(shape, data["dY"], data["x"], data["topk_idx"], data["gate"],
+                               data["W1"], data["W2"], idx, ws, out=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = B.profile_read()
+    B.profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tflops = w.useful_flop / (ms_per_step * 1e-3) / 1e12
+    kernels = {k: {"ms": v[0] / v[1], "launches": v[1]} for k, v in prof.items()}
+    gemm_flop = 2.0 * w.A * w.d_model * w.d_ff
+    dom = max((k for k in kernels if k in GEMM_LABELS), key=lambda k: kernels[k]["ms"])
+    achieved = gemm_flop / (kernels[dom]["ms"] * 1e-3) / 1e12
+    counts = idx["counts"].cpu().numpy()
+    out = {
+        "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "config": {"workload": f"{w.name}: one MoE FFN layer fwd+bwd incl. index build, T={w.T} "
+                               f"d_model={w.d_model} d_ff={w.d_ff} E={w.E} top-{w.k}, routing={w.routing}",
+                   "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
+                   "routing": w.routing,
+                   "tokens_per_expert": {"min": int(counts.min()), "max": int(counts.max())}},
+        "roofline": {"bound": "mfma", "kernel": f"gemm_bf16<{dom}>", "achieved": achieved,
+                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "flop_per_launch": gemm_flop, "avg_ms": kernels[dom]["ms"]},
+        "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, data)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,15 @@ HEXA_API hexa_status hexa_moe_bwd(const hexa_moe_shape *shape, const void *dY, c
                          size_t workspace_bytes, void *dx, float *dW1, float *db1, float *dW2,
                          float *db2, float *dgate, void *stream);
 
+/* Per-kernel timing for benchmarks (not part of the layer).  While enabled, every kernel the
+ * library launches is bracketed by two HIP events on its stream; enabling (or disabling)
+ * discards earlier records.  This is the only part of the library that creates HIP objects.
+ * hexa_moe_profile_read(i, ...) waits for the recorded events and returns the i-th distinct
+ * kernel label with its summed duration in ms and its launch count; returns 0 once i is past
+ * the last label (or on a HIP error), else 1.  Not thread-safe. */
+HEXA_API void hexa_moe_profile_enable(int on);
+HEXA_API int hexa_moe_profile_read(int i, const char **label, float *ms_total, int *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 
 HEXA_F32, HEXA_BF16 = 0, 1
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
-           "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd")
+           "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
+           "hexa_moe_profile_read")
 
 
 class Shape(ctypes.Structure):
@@ -48,6 +49,11 @@ def _load():
     lib.hexa_moe_fwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, P, Idx, P, P, S, P]
     lib.hexa_moe_bwd.restype = ctypes.c_int
     lib.hexa_moe_bwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, Idx, P, S, P, P, P, P, P, P, P]
+    lib.hexa_moe_profile_enable.restype = None
+    lib.hexa_moe_profile_enable.argtypes = [ctypes.c_int]
+    lib.hexa_moe_profile_read.restype = ctypes.c_int
+    lib.hexa_moe_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                          ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
     return lib
 
 
@@ -176,4 +182,19 @@ def hexa_moe_bwd(shape: Shape, dY, x, topk_idx, gate, W1, W2, idx, workspace: to
                             _ptr(out["dW2"], (E, f, d), torch.float32, "dW2"),
                             _ptr(out["db2"], (E, d), torch.float32, "db2"),
                             _ptr(out.get("dgate"), (T, k), torch.float32, "dgate"), _stream()))
+    return out
+
+
+def profile_enable(on: bool) -> None:
+    lib.hexa_moe_profile_enable(1 if on else 0)
+
+
+def profile_read() -> Dict[str, Tuple[float, int]]:
+    """{kernel label: (summed ms, launches)} of the launches recorded since profile_enable(True)."""
+    out = {}
+    i = 0
+    label, ms, n = ctypes.c_char_p(), ctypes.c_float(), ctypes.c_int()
+    while lib.hexa_moe_profile_read(i, ctypes.byref(label), ctypes.byref(ms), ctypes.byref(n)):
+        out[label.value.decode()] = (ms.value, n.value)
+        i += 1
     return out

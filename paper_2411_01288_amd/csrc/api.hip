@@ -2,6 +2,30 @@
 // layer (HEXA-MoE App. B Table 5).  See include/hexa_moe.h for the contract.
 #include "common.h"
 
+#include <cstring>
+#include <vector>
+
+namespace {
+
+struct ProfRec { const char* label; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
+}  // namespace
+
+void prof_begin(hipStream_t st, const char* label) {
+    if (!g_prof_on) return;
+    ProfRec r{label, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, st);
+    g_prof.push_back(r);
+}
+
+void prof_end(hipStream_t st) {
+    if (!g_prof_on || g_prof.empty()) return;
+    (void)hipEventRecord(g_prof.back().b, st);
+}
+
 namespace {
 
 constexpr int kMaxExperts = 1024;
@@ -66,6 +90,35 @@ size_t hexa_moe_workspace_bytes(const hexa_moe_shape* shape) {
     MoeDims D;
     if (check_shape(shape, &D) != HEXA_OK) return 0;
     return layout(D, shape->dtype, nullptr).total_bytes;
+}
+
+void hexa_moe_profile_enable(int on) {
+    for (ProfRec& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    g_prof.clear();
+    g_prof_on = on != 0;
+}
+
+int hexa_moe_profile_read(int i, const char** label, float* ms_total, int* launches) {
+    // distinct labels in first-seen order
+    std::vector<const char*> names;
+    for (const ProfRec& r : g_prof) {
+        bool seen = false;
+        for (const char* n : names) seen = seen || std::strcmp(n, r.label) == 0;
+        if (!seen) names.push_back(r.label);
+    }
+    if (i < 0 || i >= (int)names.size()) return 0;
+    float total = 0.f;
+    int cnt = 0;
+    for (const ProfRec& r : g_prof) {
+        if (std::strcmp(r.label, names[i]) != 0) continue;
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess) return 0;
+        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return 0;
+        total += ms;
+        ++cnt;
+    }
+    *label = names[i]; *ms_total = total; *launches = cnt;
+    return 1;
 }
 
 const char* hexa_moe_status_string(hexa_status s) {

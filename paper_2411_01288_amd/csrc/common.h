@@ -66,6 +66,16 @@ __device__ __forceinline__ SegTile seg_tile_find(const int32_t* __restrict__ off
     return s;
 }
 
+// ---- optional per-kernel timing (off unless hexa_moe_profile_enable(1)) ----
+// A ProfScope brackets one kernel launch with two HIP events on the launch stream.
+void prof_begin(hipStream_t st, const char* label);
+void prof_end(hipStream_t st);
+struct ProfScope {
+    hipStream_t st;
+    ProfScope(hipStream_t s, const char* label) : st(s) { prof_begin(s, label); }
+    ~ProfScope() { prof_end(st); }
+};
+
 // ---- internal launchers (one per translation unit), all asynchronous on `st` ----
 struct MoeDims { int T, d, f, E, k, A; };
 

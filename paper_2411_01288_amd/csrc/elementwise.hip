@@ -190,6 +190,7 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ p
 template <typename T>
 hipError_t combine_impl(int T_, int d, int k, const float* src, const int32_t* inv,
                         const float* gate, T* dst, hipStream_t st) {
+    ProfScope ps(st, gate ? "combine_y" : "combine_dx");
     constexpr int VN = Vec<T>::N;
     if (d % VN == 0) {
         const long long n = (long long)T_ * (d / VN);
@@ -221,6 +222,7 @@ template <typename T>
 hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const float* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
                                T* dout, float* dgate, hipStream_t st) {
+    ProfScope ps(st, "bwd_prologue");
     if (dgate) {  // dropped assignments keep a defined (zero) gate gradient
         const size_t n = (size_t)D.A;
         hipLaunchKernelGGL(fill_zero_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dgate, n);
@@ -235,6 +237,7 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
                                  float* partial, float* out, hipStream_t st) {
     const int max_tiles = D.A / kColsumRows + D.E;
     const int cb = ceil_div(ncols, 256);
+    ProfScope ps(st, ncols == D.d ? "colsum_db2" : "colsum_db1");
     hipLaunchKernelGGL(colsum_stage1<T>, dim3(max_tiles, cb), dim3(256), 0, st, src, ncols, D.E,
                        offsets, partial);
     hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, offsets,

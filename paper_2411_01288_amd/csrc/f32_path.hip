@@ -112,6 +112,8 @@ __global__ __launch_bounds__(256) void f32_wgrad(WgradArgs a) {
 }
 
 void rows_launch(const MoeDims& D, const RowsArgs& a, hipStream_t st) {
+    static const char* names[] = {"fc1", "fc2", "dgrad2", "dgrad1"};
+    ProfScope ps(st, names[a.mode]);
     const int max_tiles = D.A / TS + D.E;
     hipLaunchKernelGGL(f32_rows_gemm, dim3(max_tiles, ceil_div(a.N, TS)), dim3(256), 0, st, a);
 }
@@ -155,8 +157,10 @@ hipError_t launch_f32_bwd(const MoeDims& D, const float* x, const float* W1, con
     WgradArgs w{};
     w.offsets = idx.offsets; w.perm = idx.perm; w.k = D.k;
     w.A = (const float*)ws.h; w.gather = 0; w.B = (const float*)ws.dout; w.out = dW2; w.M = D.f; w.N = D.d;
-    hipLaunchKernelGGL(f32_wgrad, dim3(ceil_div(w.N, TS), ceil_div(w.M, TS), D.E), dim3(256), 0, st, w);
+    { ProfScope ps(st, "wgrad2");
+    hipLaunchKernelGGL(f32_wgrad, dim3(ceil_div(w.N, TS), ceil_div(w.M, TS), D.E), dim3(256), 0, st, w); }
     w.A = x; w.gather = 1; w.B = (const float*)ws.dpre; w.out = dW1; w.M = D.d; w.N = D.f;
-    hipLaunchKernelGGL(f32_wgrad, dim3(ceil_div(w.N, TS), ceil_div(w.M, TS), D.E), dim3(256), 0, st, w);
+    { ProfScope ps(st, "wgrad1");
+    hipLaunchKernelGGL(f32_wgrad, dim3(ceil_div(w.N, TS), ceil_div(w.M, TS), D.E), dim3(256), 0, st, w); }
     return hipGetLastError();
 }

@@ -32,7 +32,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 64;           // contraction elements per LDS stage (one 128-byte row)
+constexpr int BK = 32;           // contraction elements per LDS stage
+#ifndef HEXA_NS
+#define HEXA_NS 4
+#endif
+constexpr int NS = HEXA_NS;            // LDS stage ring depth (NS-1 stages are in flight)
 constexpr int kXcds = 8;         // workgroup i is dispatched to XCD i % 8
 constexpr int kGroupM = 8;       // row tiles per L2-sharing group
 
@@ -50,6 +54,7 @@ struct GemmArgs {
     void* out1;
     float* kpart;         // split-K slots [slot][M][N]
     int topk, E, K, N, M;
+    int a_rows;           // FC1: rows of the gathered operand (tokens T)
     int chunk_len;        // token contraction: max tokens per work item
 };
 
@@ -70,106 +75,106 @@ __device__ __forceinline__ float gelu_grad_fast(float u) {
     return sig * (1.f + 2.f * u * r * q);
 }
 
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-    return (uint32_t)(row * 128 + ((chunk ^ (row & 7)) << 4));
+// LDS image of a K-contiguous operand: row r = BK*2 bytes = CPRK chunks of 16 bytes (8 bf16 along
+// k); chunk c of row r sits at position c ^ key(r).  gfx950's LDS serves 128-bit reads 16 lanes
+// (256 bytes, 64 banks) per clock; a 32x32x16 fragment read has 16 consecutive lanes on 16
+// consecutive rows with one chunk index.  With 64-byte rows four consecutive rows fill the 256
+// bytes of bank space, so rows r, r+4, r+8, r+12 must sit on four different chunk positions:
+// key(r) = (r >> 2) & 3.  (With 128-byte rows the same argument gives (r >> 1) & 7.)
+constexpr int CPRK = BK * 2 / 16;                 // chunks per row
+constexpr int ROWB = BK * 2;                      // bytes per row
+static_assert(BK == 32 || BK == 64, "stage depth");
+__device__ __forceinline__ uint32_t lds_swz(int row) {
+    return BK == 32 ? (uint32_t)((row >> 2) & 3) : (uint32_t)((row >> 1) & 7);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Operand loaders: global -> registers (issued one stage ahead) -> LDS [R rows][64 k], swizzled.
+// Operand staging: global -> LDS without passing through registers.
+//
+// gfx950 can write a 16-byte-per-lane buffer load straight into LDS ("buffer_load_dwordx4 ... lds"):
+// the 64 lanes of one instruction fill 1024 consecutive LDS bytes in lane order, each lane
+// fetching from its own global address.  LDS stores from registers run at ~64 B/clk/CU on this
+// part, half of what a 256x256 tile needs at the MFMA rate, and cost 128 VGPRs per stage; the
+// direct path costs neither.  Because the LDS position of a lane is fixed, the bank swizzle is
+// applied on the global side: a lane fetches the chunk that belongs at its position.
+//
+// Reads past the byte range of the buffer resource return zero, which masks ragged row tails and
+// the K tail of the token contractions for free.
 // ---------------------------------------------------------------------------------------------
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef i32x4 rsrc_t;   // raw buffer resource: base[47:0], stride 0, byte range, gfx9 data format word
+typedef __attribute__((address_space(3))) void* lds_void_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// Contraction index contiguous in memory: thread owns 16-byte chunks (row q>>3, chunk q&7).
-template <int R, int NT>
-struct LoaderKC {
-    static constexpr int NLD = R * 8 / NT;   // 16-byte loads per thread and stage
-    static constexpr int NST = NLD;          // staging registers (uint4)
-    static constexpr int NOFF = NLD;         // row offsets kept per thread
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    // all four words are wave-uniform; say so, the staging instruction wants them in SGPRs
+    const uint64_t b = (uint64_t)base;
+    return rsrc_t{__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)b),
+                  __builtin_amdgcn_readfirstlane((int32_t)((uint32_t)(b >> 32) & 0xffffu)),
+                  __builtin_amdgcn_readfirstlane((int32_t)bytes), 0x00020000};
+}
+// one instruction: lane l's 16 bytes at (voff + soff) land at lds + 16*l; lds is wave-uniform.
+// Written as inline assembly on purpose: the compiler then neither tracks these loads in vmcnt nor
+// assumes that every later LDS read may alias them (which made it wait for the whole stage in
+// front of each fragment read).  The kernel waits explicitly: one "s_waitcnt vmcnt(0)" in front of
+// the barrier that hands the stage buffer over, and no other vector-memory load is in flight
+// inside the K loop.  M0 carries the LDS address (one wait state before the load reads it).
+__device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uint32_t soff) {
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds);
+    soff = __builtin_amdgcn_readfirstlane(soff);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(r), "s"(soff)
+                 : "memory");
+}
 
-    // rowoff: element offset of each owned row's start (already clamped to a valid row)
-    __device__ static __forceinline__ void gload(u32x4 (&st)[NST], const long long (&rowoff)[NOFF],
-                                                 const bf16_t* __restrict__ base, int k0, int tid) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int c = (tid + NT * i) & 7;
-            st[i] = *reinterpret_cast<const u32x4*>(base + rowoff[i] + k0 + c * 8);
-        }
+// K-contiguous operand (R rows x BK k, ROWB bytes per row in memory order along k).
+// Instruction q (= wave + NW*i) fills RPQ = 1024/ROWB rows: lane l -> row RPQ*q + l/CPRK,
+// position l%CPRK.
+template <int R, int NW>
+struct StageKC {
+    static constexpr int RPQ = 1024 / ROWB;      // rows per instruction
+    static constexpr int NI = R / RPQ / NW;      // instructions per wave and stage
+    static_assert(R % (RPQ * NW) == 0 && (RPQ * NW) % 16 == 0, "unsupported staging shape");
+    struct Lane { uint32_t voff[NI]; };          // byte offset of (row, chunk) from the resource base
+    // chunk this lane must fetch: its position XOR the swizzle key of its row (the key has period
+    // 16 rows and RPQ*NW is a multiple of 16, so it is the same for every instruction of a wave)
+    __device__ static __forceinline__ int lane_chunk(int wave, int lane) {
+        return (lane % CPRK) ^ (int)lds_swz(RPQ * wave + lane / CPRK);
     }
-    __device__ static __forceinline__ void sstore(const u32x4 (&st)[NST], uint8_t* lds, int tid) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int q = tid + NT * i;
-            *reinterpret_cast<u32x4*>(lds + lds_off(q >> 3, q & 7)) = st[i];
-        }
+    __device__ static __forceinline__ int lane_row(int wave, int lane, int i) {
+        return RPQ * (wave + NW * i) + lane / CPRK;
+    }
+    __device__ static __forceinline__ void issue(rsrc_t r, uint8_t* stage_base, int wave, uint32_t soff,
+                                                 const Lane& ln, int i) {
+        dtl16(r, stage_base + (wave + NW * i) * 1024, ln.voff[i], soff);
     }
 };
 
-// Contraction index strided in memory (row-contiguous): thread owns KR k-rows x 8 columns,
-// transposes them in registers and writes 8 LDS rows.  KR = 8 (full block) or 4 (half block,
-// used when there are fewer 8x8 blocks than threads).
-template <int R, int NT>
-struct LoaderKS {
-    static constexpr int NBLK = R;  // (R/8) * 8 blocks of 8x8
-    static constexpr bool HALF = NBLK < NT;
-    static constexpr int KR = HALF ? 4 : 8;
-    static constexpr int NB = HALF ? 1 : NBLK / NT;
-    static_assert(HALF ? (NBLK * 2 == NT) : (NBLK % NT == 0), "unsupported loader shape");
-    static constexpr int NST = NB * KR;
-    static constexpr int NOFF = 1;
-
-    // base: element (k = 0 of this stage, column 0 of the tile); ld in elements;
-    // kvalid: k-rows of this stage that exist (others read as zero); cvalid: valid columns.
-    __device__ static __forceinline__ void gload(u32x4 (&st)[NST], const bf16_t* __restrict__ base,
-                                                 long long ld, int kvalid, int cvalid, int tid) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int q = tid + NT * b;
-            const int kblk = q & 7;
-            const int rblk = HALF ? ((q >> 3) % (R / 8)) : (q >> 3);
-            const int hh = HALF ? (q / R) : 0;
-            const int col = (rblk * 8 < cvalid) ? rblk * 8 : 0;  // clamp: masked at the store
-#pragma unroll
-            for (int kk = 0; kk < KR; ++kk) {
-                const int krow = kblk * 8 + hh * 4 + kk;
-                const bool ok = krow < kvalid;
-                const int kr = ok ? krow : 0;
-                u32x4 v = *reinterpret_cast<const u32x4*>(base + (long long)kr * ld + col);
-                if (!ok) v = u32x4{0, 0, 0, 0};
-                st[b * KR + kk] = v;
-            }
-        }
+// K-strided operand (BK k-rows x R columns, a k-row is R*2 contiguous bytes in memory).
+// LDS image: k-row k at k*R*2, 16-byte chunk c (8 columns) at position c ^ ((k & 3) << 2).
+// It is read with ds_read_b64_tr_b16, which hands each lane four k-values of one column; the key
+// puts the four k-rows one 16-lane group touches on four different quarters of the bank space.
+// Instruction q fills k-rows RPI*q .. RPI*q + RPI-1 (RPI = 512 / R rows of R*2 bytes).
+template <int R, int NW>
+struct StageKS {
+    static constexpr int RB = R * 2;            // bytes per k-row
+    static constexpr int CPR = RB / 16;         // chunks per k-row
+    static constexpr int RPI = 1024 / RB;       // k-rows per instruction
+    static constexpr int NI = BK / RPI / NW;    // instructions per wave and stage
+    static_assert(RPI >= 1 && (BK / RPI) % NW == 0 && (RPI * NW) % 4 == 0 && CPR >= 16, "unsupported staging shape");
+    struct Lane { uint32_t voff; };             // byte offset of this lane's first fetch
+    __device__ static __forceinline__ Lane lane_init(int wave, int lane, uint32_t ld_bytes, int col0) {
+        const int kin = lane / CPR;                          // k-row inside the instruction
+        const int k = (RPI * wave + kin);                    // k-row of instruction i = 0
+        const int c = (lane % CPR) ^ ((k & 3) << 2);         // (RPI*NW*i is a multiple of 4)
+        return Lane{(uint32_t)k * ld_bytes + (uint32_t)(col0 + 8 * c) * 2u};
     }
-    __device__ static __forceinline__ void sstore(const u32x4 (&st)[NST], uint8_t* lds, int tid) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int q = tid + NT * b;
-            const int kblk = q & 7;
-            const int rblk = HALF ? ((q >> 3) % (R / 8)) : (q >> 3);
-            const int hh = HALF ? (q / R) : 0;
-            uint32_t w[KR][4];
-#pragma unroll
-            for (int kk = 0; kk < KR; ++kk) {
-                w[kk][0] = st[b * KR + kk].x; w[kk][1] = st[b * KR + kk].y;
-                w[kk][2] = st[b * KR + kk].z; w[kk][3] = st[b * KR + kk].w;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                const int row = rblk * 8 + j;
-                if constexpr (HALF) {
-                    u32x2 o;
-                    o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
-                    o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
-                    *reinterpret_cast<u32x2*>(lds + lds_off(row, kblk) + hh * 8) = o;
-                } else {
-                    u32x4 o;
-                    o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
-                    o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
-                    o.z = __builtin_amdgcn_perm(w[5][j >> 1], w[4][j >> 1], sel);
-                    o.w = __builtin_amdgcn_perm(w[7][j >> 1], w[6][j >> 1], sel);
-                    *reinterpret_cast<u32x4*>(lds + lds_off(row, kblk)) = o;
-                }
-            }
-        }
+    __device__ static __forceinline__ void issue(rsrc_t r, uint8_t* stage_base, int wave, uint32_t ld_bytes,
+                                                 uint32_t soff, const Lane& ln, int i) {
+        dtl16(r, stage_base + (wave + NW * i) * 1024, ln.voff, soff + (uint32_t)(RPI * NW * i) * ld_bytes);
     }
 };
 
@@ -179,6 +184,9 @@ struct LoaderKS {
 
 // XCD-aware id: the G logical items are cut into 8 contiguous ranges, one per XCD.
 __device__ __forceinline__ int xcd_remap(int wg, int G) {
+#ifdef HEXA_DBG_NOXCD
+    return wg < G ? wg : -1;
+#endif
     const int per = ceil_div(G, kXcds);
     const int xcd = wg % kXcds, loc = wg / kXcds;
     if (loc >= per) return -1;
@@ -199,36 +207,27 @@ __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& til
 
 struct TokenItem { int e, kbeg, kend, tile_m, tile_n, nchunks, slot; };
 
-// Token-contraction items: expert-major, chunk, then tiles.  slot = index into the split-K
-// partial buffer (only used when the expert has more than one chunk).
+// Token-contraction items, numbered expert-major then chunk: item `ec` covers perm rows
+// [kbeg, kend) of one expert.  slot = index into the split-K partial buffer (only used when the
+// expert has more than one chunk).  e = -1 past the last item.
 __device__ __forceinline__ TokenItem token_item_find(const int32_t* __restrict__ offsets, int E,
-                                                     int L, int tm, int tn, int pid) {
+                                                     int L, int tm, int tn, int ec, int tile) {
     TokenItem it{-1, 0, 0, 0, 0, 0, 0};
     int acc = 0, slot = 0;
-    const int tmn = tm * tn;
     for (int e = 0; e < E; ++e) {
         const int b = offsets[e], n = offsets[e + 1] - b;
         const int nch = ceil_div(n, L);
-        const int items = nch * tmn;
-        if (pid < acc + items) {
-            const int local = pid - acc;
-            const int c = local / tmn;
+        if (ec < acc + nch) {
+            const int c = ec - acc;
             it.e = e; it.nchunks = nch; it.slot = slot + c;
             it.kbeg = b + c * L; it.kend = min(b + n, it.kbeg + L);
-            grouped_tile(local - c * tmn, tm, tn, it.tile_m, it.tile_n);
+            grouped_tile(tile, tm, tn, it.tile_m, it.tile_n);
             return it;
         }
-        acc += items;
+        acc += nch;
         if (nch > 1) slot += nch;
     }
     return it;
-}
-
-__device__ __forceinline__ int token_items_total(const int32_t* __restrict__ offsets, int E, int L,
-                                                 int tmn) {
-    int total = 0;
-    for (int e = 0; e < E; ++e) total += ceil_div(offsets[e + 1] - offsets[e], L) * tmn;
-    return total;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -241,10 +240,11 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     constexpr int FM = TM / 32, FN = TN / 32;
     constexpr bool TOKENS = (OP == OP_WGRAD2 || OP == OP_WGRAD1);
     constexpr bool B_KS = TOKENS || OP == OP_FC1 || OP == OP_FC2;
-    constexpr int STAGE = (BM + BN) * 128;
+    constexpr int STAGE = (BM + BN) * ROWB;   // bytes of one LDS stage (A image, then B image)
+    constexpr int SPS = BK / 16;              // k-substeps (one MFMA k each) per stage
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of 32x32");
 
-    extern __shared__ __align__(16) uint8_t smem[];
+    extern __shared__ __align__(1024) uint8_t smem[];   // two stage buffers
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -256,21 +256,38 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     int kbeg = 0, kend = 0;           // token contraction: perm rows of this item
     float* tok_out = nullptr;         // token contraction: where the tile goes
     if constexpr (!TOKENS) {
+#ifdef HEXA_DBG_UNIFORM
+        const int tm_total = 1024;
+#else
         const int tm_total = seg_tiles_total(g.offsets, g.E, BM);
+#endif
         const int tn = ceil_div(g.N, BN);
         const int pid = xcd_remap(blockIdx.x, tm_total * tn);
         if (pid < 0) return;
         int tile_m, tile_n;
         grouped_tile(pid, tm_total, tn, tile_m, tile_n);
+#ifdef HEXA_DBG_SAMETILE
+        tile_m = HEXA_DBG_SAMETILE == 1 ? 0 : (tile_m % HEXA_DBG_SAMETILE); tile_n = HEXA_DBG_SAMETILE == 1 ? 0 : tile_n;
+#endif
+#ifdef HEXA_DBG_UNIFORM
+        const SegTile s{tile_m / 16, tile_m * 256, 256};
+#else
         const SegTile s = seg_tile_find(g.offsets, g.E, BM, tile_m);
+#endif
         e = s.e; m0 = s.row0; mvalid = s.rows; n0 = tile_n * BN;
         nk = g.K / BK;
     } else {
+        // every (expert, chunk) item is a set of tm*tn tiles over the same tokens; each XCD takes
+        // an eighth of every item's tiles (neighbouring ones), so the XCDs stay balanced however
+        // uneven the experts are, and the whole chip streams the same token rows at a time
         const int tm = ceil_div(g.M, BM), tn = ceil_div(g.N, BN);
-        const int G = token_items_total(g.offsets, g.E, g.chunk_len, tm * tn);
-        const int pid = xcd_remap(blockIdx.x, G);
-        if (pid < 0) return;
-        const TokenItem it = token_item_find(g.offsets, g.E, g.chunk_len, tm, tn, pid);
+        const int tmn = tm * tn;
+        const int per = ceil_div(tmn, kXcds);
+        const int xcd = blockIdx.x % kXcds, loc = blockIdx.x / kXcds;
+        const int tile = xcd * per + loc % per;
+        if (tile >= tmn) return;
+        const TokenItem it = token_item_find(g.offsets, g.E, g.chunk_len, tm, tn, loc / per, tile);
+        if (it.e < 0) return;
         e = it.e; m0 = it.tile_m * BM; n0 = it.tile_n * BN; mvalid = min(BM, g.M - m0);
         kbeg = it.kbeg; kend = it.kend;
         nk = ceil_div(kend - kbeg, BK);
@@ -279,62 +296,71 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     }
     const int nvalid = min(BN, g.N - n0);
 
-    // ---- loaders ----------------------------------------------------------------------------
-    using LA = typename std::conditional<TOKENS, LoaderKS<BM, NT>, LoaderKC<BM, NT>>::type;
-    using LB = typename std::conditional<B_KS, LoaderKS<BN, NT>, LoaderKC<BN, NT>>::type;
-    u32x4 sta[LA::NST], stb[LB::NST];
-    long long offa[LA::NOFF], offb[LB::NOFF];
-    const bf16_t* a_base;
-    const bf16_t* b_base;
-    long long a_ld = 0, b_ld = 0;
+#ifndef HEXA_DBG_PADA
+#define HEXA_DBG_PADA 0
+#endif
+#ifndef HEXA_DBG_PADB
+#define HEXA_DBG_PADB 0
+#endif
+    // ---- staging set-up -----------------------------------------------------------------------
+    constexpr int NW = WM * WN;
+    using SA = typename std::conditional<TOKENS, StageKS<BM, NW>, StageKC<BM, NW>>::type;
+    using SB = typename std::conditional<B_KS, StageKS<BN, NW>, StageKC<BN, NW>>::type;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    typename SA::Lane lna;
+    typename SB::Lane lnb;
+    rsrc_t ra, rb;
+    uint32_t a_step, b_step;      // bytes one K-step advances each operand
+    uint32_t a_ld = 0, b_ld = 0;  // row pitch in bytes of the K-strided operands
     if constexpr (!TOKENS) {
-        a_base = g.A;
+        // FC1 gathers token rows of x through the re-index vector; the other row GEMMs read
+        // perm-ordered rows, and rows past the segment fall outside the resource (zeros)
+        if constexpr (OP == OP_FC1) ra = make_rsrc(g.A, (uint32_t)g.a_rows * (uint32_t)g.K * 2u);
+        else ra = make_rsrc(g.A + (size_t)m0 * (g.K + HEXA_DBG_PADA), (uint32_t)mvalid * (uint32_t)(g.K + HEXA_DBG_PADA) * 2u);
+        a_step = BK * 2;
+        const uint32_t ca = (uint32_t)SA::lane_chunk(uwave, lane) * 16u;
 #pragma unroll
-        for (int i = 0; i < LA::NLD; ++i) {
-            int r = (tid + NT * i) >> 3;
-            if (r >= mvalid) r = 0;  // rows past the segment: read a valid row, never stored
-            long long src = m0 + r;
-            if constexpr (OP == OP_FC1) src = g.perm[m0 + r] / g.topk;
-            offa[i] = src * g.K;
+        for (int i = 0; i < SA::NI; ++i) {
+            uint32_t r = (uint32_t)SA::lane_row(uwave, lane, i);
+            if constexpr (OP == OP_FC1) r = (uint32_t)(g.perm[m0 + ((int)r < mvalid ? (int)r : 0)] / g.topk);
+            lna.voff[i] = r * (uint32_t)(g.K + HEXA_DBG_PADA) * 2u + ca;
         }
         if constexpr (B_KS) {  // W[e][K][N]
-            b_base = g.B + (size_t)e * g.K * g.N + n0;
-            b_ld = g.N;
-        } else {               // W[e][N][K]
-            b_base = g.B + (size_t)e * g.N * g.K;
+            b_ld = (uint32_t)g.N * 2u;
+            rb = make_rsrc(g.B + (size_t)e * g.K * g.N, (uint32_t)g.K * b_ld);
+            b_step = BK * b_ld;
+            lnb = SB::lane_init(uwave, lane, b_ld, n0);
+        } else {               // W[e][N][K]: rows past N fall outside the resource
+            rb = make_rsrc(g.B + ((size_t)e * g.N + n0) * (g.K + HEXA_DBG_PADB), (uint32_t)nvalid * (uint32_t)(g.K + HEXA_DBG_PADB) * 2u);
+            b_step = BK * 2;
+            const uint32_t cb = (uint32_t)SB::lane_chunk(uwave, lane) * 16u;
 #pragma unroll
-            for (int i = 0; i < LB::NLD; ++i) {
-                int r = (tid + NT * i) >> 3;
-                if (r >= nvalid) r = 0;
-                offb[i] = (long long)(n0 + r) * g.K;
-            }
+            for (int i = 0; i < SB::NI; ++i)
+                lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)(g.K + HEXA_DBG_PADB) * 2u + cb;
         }
     } else {
-        a_base = g.A + (size_t)kbeg * g.M + m0; a_ld = g.M;
-        b_base = g.B + (size_t)kbeg * g.N + n0; b_ld = g.N;
+        // both operands are [tokens][features] in perm order; tokens past this item's range fall
+        // outside the resources
+        a_ld = (uint32_t)g.M * 2u; b_ld = (uint32_t)g.N * 2u;
+        ra = make_rsrc(g.A + (size_t)kbeg * g.M, (uint32_t)(kend - kbeg) * a_ld);
+        rb = make_rsrc(g.B + (size_t)kbeg * g.N, (uint32_t)(kend - kbeg) * b_ld);
+        a_step = BK * a_ld; b_step = BK * b_ld;
+        if constexpr (TOKENS) {
+            lna = SA::lane_init(uwave, lane, a_ld, m0);
+            lnb = SB::lane_init(uwave, lane, b_ld, n0);
+        }
     }
-
-#define LOAD_STAGE(kt_)                                                                          \
+    // one staging instruction of operand A / B for K-step kt_ into LDS stage buffer buf_
+#define ISSUE_A(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
-        const int kt__ = (kt_);                                                                  \
-        if constexpr (!TOKENS) {                                                                 \
-            LA::gload(sta, offa, a_base, kt__ * BK, tid);                                        \
-            if constexpr (B_KS)                                                                  \
-                LB::gload(stb, b_base + (size_t)kt__ * BK * b_ld, b_ld, BK, nvalid, tid);        \
-            else                                                                                 \
-                LB::gload(stb, offb, b_base, kt__ * BK, tid);                                    \
-        } else {                                                                                 \
-            const int kv__ = min(BK, kend - kbeg - kt__ * BK);                                   \
-            LA::gload(sta, a_base + (size_t)kt__ * BK * a_ld, a_ld, kv__, mvalid, tid);          \
-            LB::gload(stb, b_base + (size_t)kt__ * BK * b_ld, b_ld, kv__, nvalid, tid);          \
-        }                                                                                        \
+        if constexpr (TOKENS) SA::issue(ra, (buf_), uwave, a_ld, (kt_) * a_step, lna, i_);       \
+        else SA::issue(ra, (buf_), uwave, (kt_) * a_step, lna, i_);                              \
     } while (0)
-#define STORE_STAGE(buf_)                                                                        \
+#define ISSUE_B(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
-        LA::sstore(sta, smem + (buf_) * STAGE, tid);                                             \
-        LB::sstore(stb, smem + (buf_) * STAGE + BM * 128, tid);                                  \
+        if constexpr (B_KS) SB::issue(rb, (buf_) + BM * ROWB, uwave, b_ld, (kt_) * b_step, lnb, i_); \
+        else SB::issue(rb, (buf_) + BM * ROWB, uwave, (kt_) * b_step, lnb, i_);                   \
     } while (0)
-    (void)offa; (void)offb; (void)a_ld;
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -344,74 +370,238 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // per-lane fragment addresses: row (wave tile row + l32), chunk (2 s + hi) ^ (l32 & 7)
-    const uint32_t a_row_off = (uint32_t)((wm * TM + l32) * 128);
-    const uint32_t b_row_off = (uint32_t)(BM * 128 + (wn * TN + l32) * 128);
-    uint32_t coff[4];
+    // ---- per-lane fragment addresses -----------------------------------------------------------
+    // K-contiguous image: 128-bit read of row (wave tile row + l32), chunk (2s + hi) ^ key(l32)
+    // (wave tile rows and fragment rows are multiples of 32, so key(row) = key(l32)).
+    // K-strided image: two transposing 64-bit reads per fragment; in a group of 16 lanes, lane s
+    // addresses k-row (s >> 2) and columns 4*(s & 3).., and receives column (s) of the group's 16,
+    // k-rows 0..3 (see StageKS).  Both give a lane k = 16s + 8hi + 0..7 of its row/column.
+    constexpr int A_RB = BM * 2, B_RB = BN * 2;  // LDS k-row pitch of the K-strided images
+    uint32_t aoff[4], boff[4];                   // KC: per k-substep; KS: per fragment
+    uint32_t a_ks = 0, b_ks = 0;                 // KS lane base
+    {
+        const int s16 = lane & 15, grp = lane >> 4;
+        const int krel = s16 >> 2, dlt = 2 * (grp & 1) + ((s16 & 3) >> 1), half8 = (s16 & 1) * 8;
+        if constexpr (TOKENS) {
+            a_ks = (uint32_t)((8 * hi + krel) * A_RB + dlt * 16 + half8);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) coff[s] = (uint32_t)(((2 * s + hi) ^ (l32 & 7)) << 4);
-
-    if (nk > 0) {
-        LOAD_STAGE(0);
-        STORE_STAGE(0);
-        if (nk > 1) LOAD_STAGE(1);
-    }
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const uint8_t* sbase = smem + cur * STAGE;
-        if (kt + 1 < nk) STORE_STAGE(cur ^ 1);   // registers hold stage kt+1
-        if (kt + 2 < nk) LOAD_STAGE(kt + 2);
+            for (int i = 0; i < 4; ++i)
+                aoff[i] = (uint32_t)((((wm * TM) / 8 + 4 * i) ^ (krel << 2)) * 16);
+        } else {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8 af[FM], bfr[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(sbase + a_row_off + i * 32 * 128 + coff[s]);
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(sbase + b_row_off + j * 32 * 128 + coff[s]);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int s = 0; s < 4; ++s)
+                aoff[s] = (uint32_t)((wm * TM + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
         }
-        __syncthreads();
+        if constexpr (B_KS) {
+            b_ks = (uint32_t)(BM * ROWB + (8 * hi + krel) * B_RB + dlt * 16 + half8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                boff[j] = (uint32_t)((((wn * TN) / 8 + 4 * j) ^ (krel << 2)) * 16);
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                boff[s] = (uint32_t)(BM * ROWB + (wn * TN + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
+        }
     }
+    static_assert(FM <= 4 && FN <= 4, "fragment offset tables hold four entries");
 
-#undef LOAD_STAGE
-#undef STORE_STAGE
+    // two fragment sets: set (s & 1) is multiplied while the other one is being read
+    bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
+// timing-only ablation switches (never defined in the library build)
+#ifdef HEXA_DBG_NOGLOBAL
+#define DBG_LOAD(x)
+#else
+#define DBG_LOAD(x) x
+#endif
+#ifdef HEXA_DBG_NOMFMA
+#define DBG_MFMA(stmt_) if (m == 0 && tid == 1023) { stmt_; }
+#else
+#define DBG_MFMA(stmt_) stmt_
+#endif
+#ifdef HEXA_DBG_NOREAD
+#define DBG_READ(x)
+#else
+#define DBG_READ(x) x
+#endif
+#define TR_READ(p_) __builtin_bit_cast(s16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p_)))
+    // LDS reads of one k-substep are numbered: A fragments first, then B fragments; a K-strided
+    // fragment takes two reads (k-rows +0..3 and +4..7), a K-contiguous one takes one.
+    constexpr int RA = TOKENS ? 2 : 1, RBn = B_KS ? 2 : 1;
+    constexpr int NRD = FM * RA + FN * RBn;
+    s16x4 tra[FM], trb[FN];   // first halves of K-strided fragments
+#define READ_ONE(fa, fb, base_, s_, m_)                                                          \
+    do {                                                                                         \
+        if ((m_) < FM * RA) {                                                                    \
+            const int i_ = (m_) / RA;                                                            \
+            if constexpr (TOKENS) {                                                              \
+                const uint8_t* p_ = (base_) + a_ks + aoff[i_] + (16 * (s_) + 4 * ((m_) % RA)) * A_RB; \
+                if ((m_) % RA == 0) tra[i_] = TR_READ(p_);                                       \
+                else fa[i_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(tra[i_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
+            } else {                                                                             \
+                fa[i_] = *reinterpret_cast<const bf16x8*>((base_) + aoff[s_] + i_ * 32 * ROWB);   \
+            }                                                                                    \
+        } else if ((m_) < NRD) {                                                                 \
+            const int mb_ = (m_) - FM * RA;                                                      \
+            const int j_ = mb_ / RBn;                                                            \
+            if constexpr (B_KS) {                                                                \
+                const uint8_t* p_ = (base_) + b_ks + boff[j_] + (16 * (s_) + 4 * (mb_ % RBn)) * B_RB; \
+                if (mb_ % RBn == 0) trb[j_] = TR_READ(p_);                                       \
+                else fb[j_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(trb[j_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
+            } else {                                                                             \
+                fb[j_] = *reinterpret_cast<const bf16x8*>((base_) + boff[s_] + j_ * 32 * ROWB);   \
+            }                                                                                    \
+        }                                                                                        \
+    } while (0)
 
-    // ---- epilogue: lane holds column l32 of each 32x32 block, rows 8 q + 4 hi + (r & 3) ------
+    constexpr int NM = FM * FN;   // MFMAs per k-substep and wave
+    static_assert(NRD <= NM, "fragment reads must fit the substep");
+    constexpr int ND = SA::NI + SB::NI;          // staging instructions per wave and stage
+    constexpr int TS = (SPS - 1) * NM;           // slots they are spread over (all but the last substep)
+    // staging instruction number o_ of the next stage: A's first, then B's
+#define ISSUE_ANY(buf_, kt_, o_)                                                                 \
+    do {                                                                                         \
+        if ((o_) < SA::NI) ISSUE_A(buf_, kt_, (o_) < SA::NI ? (o_) : 0);                         \
+        else ISSUE_B(buf_, kt_, (o_) >= SA::NI ? (o_) - SA::NI : 0);                             \
+    } while (0)
+    // staging instructions of global slot g_ (0 .. TS-1): numbers [g*ND/TS, (g+1)*ND/TS)
+#define SPREAD(g_, buf_, kt_)                                                                    \
+    do {                                                                                         \
+        _Pragma("unroll") for (int o = 0; o < ND; ++o)                                           \
+            if (o >= (g_) * ND / TS && o < ((g_) + 1) * ND / TS) ISSUE_ANY(buf_, kt_, o);        \
+    } while (0)
+    // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
+    // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
+    // tile row (l32) and 4 consecutive tile columns per register quad, which the epilogue stores
+    // as 8- or 16-byte vectors.
+    // One k-substep: NM MFMAs on fragment set (fa, fb); after MFMA m, memory slot m is issued
+    // (one fragment read for the next substep, and a share of the staging instructions), so the
+    // LDS and vector-memory queues are fed a little at a time while the matrix pipe stays busy:
+    // one wavefront per SIMD has nobody else to hide a burst behind.
+#define SUBSTEP(fa, fb, READ_, EXTRA_)                                                           \
+    do {                                                                                         \
+        _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                         \
+            DBG_MFMA(acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(              \
+                fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0));                          \
+            FENCE();                                                                             \
+            READ_;                                                                               \
+            EXTRA_;                                                                              \
+            FENCE();                                                                             \
+        }                                                                                        \
+    } while (0)
+    // wait until at most the NS-2 youngest stages of this wave's staging loads are outstanding
+#define WAIT_STAGE() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ND * (NS - 2)) : "memory")
+    static_assert(ND * (NS - 2) <= 63, "vmcnt is a 6-bit counter");
+
+    // Ring of NS stage buffers: stage j lives in buffer j % NS.  Prologue: request stages 0..NS-2.
+    const int klast = nk > 0 ? nk - 1 : 0;
+    if (nk > 0) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int col = wn * TN + j * 32 + l32;
-        const bool cok = col < nvalid;
-        const int n = n0 + col;
-        float bias = 0.f;
-        if constexpr (OP == OP_FC1 || OP == OP_FC2)
-            if (cok) bias = bf2f(g.bias[(size_t)e * g.N + n]);
+        for (int j = 0; j < NS - 1; ++j) {
+            uint8_t* buf = smem + j * STAGE;
+            const uint32_t kj = (uint32_t)min(j, klast);
+            _Pragma("unroll") for (int o = 0; o < ND; ++o) ISSUE_ANY(buf, kj, o);
+        }
+    }
+    WAIT_STAGE();
+    __syncthreads();
+    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa0, fb0, smem, 0, m);
+#ifdef HEXA_DBG_NOREAD
+    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa1, fb1, smem, 1, m);
+#endif
+
+    // One K-step (stage kt, BK = SPS*16 contraction elements).  While buffer kt % NS is multiplied,
+    // stage kt+NS-1 is requested into buffer (kt-1) % NS, which nobody reads any more: its last
+    // fragment reads were issued before the barrier of K-step kt-1.  Before the last substep the
+    // wave waits for its share of stage kt+1 and the barrier publishes that stage, whose first
+    // fragments are then read during the last substep.  Past the last stage the requests re-fetch
+    // the last stage into buffers nobody reads, which keeps the loop body free of branches.
+    int cur = 0;                                  // kt % NS
+    for (int kt = 0; kt < nk; ++kt) {
+        uint8_t* sbase = smem + cur * STAGE;
+        const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
+        const int prv = (cur == 0) ? NS - 1 : cur - 1;
+        uint8_t* nbase = smem + nxt * STAGE;
+        uint8_t* pbase = smem + prv * STAGE;
+        const uint32_t kreq = (uint32_t)min(kt + NS - 1, klast);
+        FENCE();
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
+        for (int ss = 0; ss < SPS; ++ss) {
+            if (ss + 1 < SPS) {
+                if ((ss & 1) == 0)
+                    SUBSTEP(fa0, fb0, DBG_READ(READ_ONE(fa1, fb1, sbase, ss + 1, m)),
+                            DBG_LOAD(SPREAD(ss * NM + m, pbase, kreq)));
+                else
+                    SUBSTEP(fa1, fb1, DBG_READ(READ_ONE(fa0, fb0, sbase, ss + 1, m)),
+                            DBG_LOAD(SPREAD(ss * NM + m, pbase, kreq)));
+            } else {
+                WAIT_STAGE();
+                __syncthreads();
+                FENCE();
+                if ((ss & 1) == 0) SUBSTEP(fa0, fb0, DBG_READ(READ_ONE(fa1, fb1, nbase, 0, m)), (void)0);
+                else SUBSTEP(fa1, fb1, DBG_READ(READ_ONE(fa0, fb0, nbase, 0, m)), (void)0);
+            }
+        }
+        cur = nxt;
+    }
+    // no staging write may still be in flight when the workgroup gives its LDS back
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef WAIT_STAGE
+#undef ISSUE_ANY
+#undef SUBSTEP
+#undef SPREAD
+#undef READ_ONE
+#undef TR_READ
+#undef FENCE
+#undef ISSUE_A
+#undef ISSUE_B
+
+    // ---- epilogue: in block (i, j) a lane holds row i*32 + l32 and, in register quad q, the four
+    // columns j*32 + 8q + 4hi + 0..3 -------------------------------------------------------------
+    const size_t ldo = (size_t)g.N;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * TM + i * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-                if (!cok || row >= mvalid) continue;
-                const float v = acc[i][j][r] + bias;
+    for (int i = 0; i < FM; ++i) {
+        const int row = wm * TM + i * 32 + l32;
+        const bool rok = row < mvalid;
+        const size_t orow = (size_t)(m0 + row) * ldo + (size_t)n0;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = wn * TN + j * 32 + 8 * q + 4 * hi;
+#ifdef HEXA_DBG_NOEPI
+                if (acc[i][j][4 * q] != 12345.f) continue;
+#endif
+                if (!rok || col >= nvalid) continue;
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
+                if constexpr (OP == OP_FC1 || OP == OP_FC2) {
+                    const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + n0 + col);
+                    v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
+                    v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                }
+                const size_t oi = orow + col;
                 if constexpr (TOKENS) {
-                    tok_out[(size_t)(m0 + row) * g.N + n] = v;
+                    *reinterpret_cast<float4*>(tok_out + oi) = make_float4(v[0], v[1], v[2], v[3]);
+                } else if constexpr (OP == OP_FC1) {
+                    u32x2 p, h;
+                    p.x = pack_bf2(v[0], v[1]); p.y = pack_bf2(v[2], v[3]);
+                    h.x = pack_bf2(gelu_fast(v[0]), gelu_fast(v[1]));
+                    h.y = pack_bf2(gelu_fast(v[2]), gelu_fast(v[3]));
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = p;
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out1) + oi) = h;
+                } else if constexpr (OP == OP_DGRAD2) {
+                    const u32x2 pp = *reinterpret_cast<const u32x2*>(g.pre_in + oi);
+                    const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
+                    const float p2 = __uint_as_float(pp.y << 16), p3 = __uint_as_float(pp.y & 0xffff0000u);
+                    u32x2 d;
+                    d.x = pack_bf2(v[0] * gelu_grad_fast(p0), v[1] * gelu_grad_fast(p1));
+                    d.y = pack_bf2(v[2] * gelu_grad_fast(p2), v[3] * gelu_grad_fast(p3));
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d;
                 } else {
-                    const size_t oi = (size_t)(m0 + row) * g.N + n;
-                    if constexpr (OP == OP_FC1) {
-                        reinterpret_cast<bf16_t*>(g.out0)[oi] = f2bf(v);
-                        reinterpret_cast<bf16_t*>(g.out1)[oi] = f2bf(gelu_fast(v));
-                    } else if constexpr (OP == OP_DGRAD2) {
-                        reinterpret_cast<bf16_t*>(g.out0)[oi] = f2bf(v * gelu_grad_fast(bf2f(g.pre_in[oi])));
-                    } else {
-                        reinterpret_cast<float*>(g.out0)[oi] = v;
-                    }
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.out0) + oi) =
+                        make_float4(v[0], v[1], v[2], v[3]);
                 }
             }
         }
@@ -448,9 +638,10 @@ __global__ __launch_bounds__(256) void wgrad_finish(const int32_t* __restrict__ 
 constexpr int kNumCUs = 256;
 
 template <int BM, int BN, int WM, int WN, int OP>
-void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st) {
+void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label) {
+    ProfScope ps(st, label);
     auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
-    constexpr int lds = 2 * (BM + BN) * 128;
+    constexpr int lds = NS * (BM + BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -464,9 +655,10 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st) {
 }
 
 template <int BM, int BN, int WM, int WN, int OP>
-void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st) {
+void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label,
+                   const char* label_fin) {
     auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
-    constexpr int lds = 2 * (BM + BN) * 128;
+    constexpr int lds = NS * (BM + BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -475,8 +667,12 @@ void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st) {
     }
     const int tmn = ceil_div(g.M, BM) * ceil_div(g.N, BN);
     const int chunks_max = D.A / g.chunk_len + D.E;
-    const int grid = kXcds * ceil_div(chunks_max * tmn, kXcds);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+    const int grid = kXcds * ceil_div(tmn, kXcds) * chunks_max;
+    {
+        ProfScope ps(st, label);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+    }
+    ProfScope ps(st, label_fin);
     const size_t mn = (size_t)g.M * g.N;
     const int gx = (int)((mn / 4 + 255) / 256 < 1024 ? (mn / 4 + 255) / 256 : 1024);
     hipLaunchKernelGGL(wgrad_finish, dim3(gx, D.E), dim3(256), 0, st, g.offsets, D.E, g.chunk_len, mn,
@@ -508,10 +704,10 @@ hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
                            const MoeWorkspace& ws, hipStream_t st) {
     GemmArgs g{};
     g.offsets = idx.offsets; g.perm = idx.perm; g.topk = D.k; g.E = D.E;
-    g.A = x; g.B = W1; g.bias = b1; g.out0 = ws.pre; g.out1 = ws.h; g.K = D.d; g.N = D.f;
-    launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st);
+    g.A = x; g.a_rows = D.T; g.B = W1; g.bias = b1; g.out0 = ws.pre; g.out1 = ws.h; g.K = D.d; g.N = D.f;
+    launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st, "fc1");
     g.A = (const bf16_t*)ws.h; g.B = W2; g.bias = b2; g.out0 = ws.o; g.out1 = nullptr; g.K = D.f; g.N = D.d;
-    launch_rows<TBM, TBN, TWM, TWN, OP_FC2>(D, g, st);
+    launch_rows<TBM, TBN, TWM, TWN, OP_FC2>(D, g, st, "fc2");
     return hipGetLastError();
 }
 
@@ -524,15 +720,15 @@ hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     // dpre = (do W2^T) * GELU'(pre)
     g.A = (const bf16_t*)ws.dout; g.B = W2; g.pre_in = (const bf16_t*)ws.pre; g.out0 = ws.dpre;
     g.K = D.d; g.N = D.f;
-    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD2>(D, g, st);
+    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD2>(D, g, st, "dgrad2");
     // dW2[e] = h^T do
     g.A = (const bf16_t*)ws.h; g.B = (const bf16_t*)ws.dout; g.out0 = dW2; g.M = D.f; g.N = D.d;
-    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD2>(D, g, st);
+    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD2>(D, g, st, "wgrad2", "wgrad2_finish");
     // dxp = dpre W1^T
     g.A = (const bf16_t*)ws.dpre; g.B = W1; g.out0 = ws.dxp; g.K = D.f; g.N = D.d;
-    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD1>(D, g, st);
+    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD1>(D, g, st, "dgrad1");
     // dW1[e] = xg^T dpre
     g.A = xg; g.B = (const bf16_t*)ws.dpre; g.out0 = dW1; g.M = D.d; g.N = D.f;
-    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD1>(D, g, st);
+    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD1>(D, g, st, "wgrad1", "wgrad1_finish");
     return hipGetLastError();
 }

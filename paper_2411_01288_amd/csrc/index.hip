@@ -171,11 +171,14 @@ hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx 
     int32_t* hist = (int32_t*)scratch;
     const int nwg = ceil_div(p.nchunks, kWavesPerWg);
     const size_t lds = (size_t)kWavesPerWg * D.E * sizeof(int32_t);
+    { ProfScope ps(st, "index_count");
     hipLaunchKernelGGL(index_count, dim3(nwg), dim3(256), lds, st, topk_idx, D.A, D.E,
-                       p.rows_per_wave, p.nchunks, hist);
+                       p.rows_per_wave, p.nchunks, hist); }
+    { ProfScope ps(st, "index_scan");
     hipLaunchKernelGGL(index_scan, dim3(1), dim3(1024), 0, st, hist, D.E, p.nchunks, out.counts,
-                       out.offsets);
+                       out.offsets); }
+    { ProfScope ps(st, "index_scatter");
     hipLaunchKernelGGL(index_scatter, dim3(nwg), dim3(256), lds, st, topk_idx, D.A, D.E,
-                       p.rows_per_wave, p.nchunks, hist, out.offsets, out.perm, out.inv);
+                       p.rows_per_wave, p.nchunks, hist, out.offsets, out.perm, out.inv); }
     return hipGetLastError();
 }
