@@ -23,9 +23,9 @@
  *   - Errors are return codes; argument checks run on the host before any
  *     launch, so a non-OK return means nothing was enqueued.
  *   - HEXA_BF16 needs d % 64 == 0 and f % 64 == 0 (the paper's kernels likewise
- *     assume feature sizes divisible by the tile, App. B); HEXA_F32 takes any
- *     positive sizes.  E <= 1024.  A < 2^31 / max(d, f) is not required: row
- *     offsets are 64-bit.
+ *     assume feature sizes divisible by the tile, App. B), T*d*2 < 2^32 and
+ *     d*f*2 < 2^32 (32-bit byte offsets inside x and inside one expert's weight
+ *     matrix); HEXA_F32 takes any positive sizes.  E <= 1024.
  *   - Expert ids must satisfy 0 <= topk_idx < E (App. B Table 4).  An id outside
  *     that range is not an error return (the host cannot see it): that
  *     assignment is dropped from the index (inv = -1, offsets[E] < A), it
@@ -48,7 +48,7 @@ typedef enum {
     HEXA_OK = 0,
     HEXA_ERR_NULL = 1,        /* a required pointer is NULL */
     HEXA_ERR_SHAPE = 2,       /* a size is <= 0, A overflows int32, or E > 1024 */
-    HEXA_ERR_UNSUPPORTED = 3, /* dtype unknown, or bf16 with d or f not a multiple of 64 */
+    HEXA_ERR_UNSUPPORTED = 3, /* dtype unknown, or a bf16 size rule (see above) is not met */
     HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query */
     HEXA_ERR_DEVICE = 5       /* a launch failed (hipGetLastError) */
 } hexa_status;

@@ -36,7 +36,14 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (s->E > kMaxExperts) return HEXA_ERR_SHAPE;
     if ((long long)s->T * s->k > 0x7fffffffLL) return HEXA_ERR_SHAPE;
     if (s->dtype != HEXA_F32 && s->dtype != HEXA_BF16) return HEXA_ERR_UNSUPPORTED;
-    if (s->dtype == HEXA_BF16 && (s->d_model % 64 != 0 || s->d_ff % 64 != 0)) return HEXA_ERR_UNSUPPORTED;
+    if (s->dtype == HEXA_BF16) {
+        if (s->d_model % 64 != 0 || s->d_ff % 64 != 0) return HEXA_ERR_UNSUPPORTED;
+        // the bf16 kernels address x (gathered rows) and one expert's weight matrix with 32-bit
+        // byte offsets
+        if ((unsigned long long)s->T * s->d_model * 2ull > 0xffffffffull ||
+            (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull)
+            return HEXA_ERR_UNSUPPORTED;
+    }
     D->T = s->T; D->d = s->d_model; D->f = s->d_ff; D->E = s->E; D->k = s->k; D->A = s->T * s->k;
     return HEXA_OK;
 }

@@ -690,6 +690,9 @@ int wgrad_chunk_len(const MoeDims& D) {
     long long L = (long long)D.A * tmn / (4 * kNumCUs);
     L = (L + 63) / 64 * 64;
     if (L < 1024) L = 1024;
+    // one item's rows are addressed with 32-bit byte offsets: L * max(d, f) * 2 < 2^32
+    const long long cap = (0xffffffffLL / (2LL * (D.d > D.f ? D.d : D.f))) / 64 * 64;
+    if (L > cap) L = cap;
     return (int)L;
 }
 

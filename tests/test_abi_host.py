@@ -1,0 +1,81 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2411_01288_amd import build as bld
+    if not os.path.exists(bld.LIB):
+        bld.build_library()
+    from paper_2411_01288_amd import binding
+    return binding
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "hexa_moe.h")).read()
+    return sorted(set(re.findall(r"HEXA_API[^;(]*?\b(hexa_moe_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = header_functions()
+    assert len(names) >= 8
+    assert sorted(B.EXPORTS) == names
+    for n in names:
+        assert getattr(B.lib, n) is not None
+
+
+def test_size_queries_and_shape_validation(B):
+    ok = B.make_shape(4096, 384, 1536, 8, 2, "bf16")
+    assert B.workspace_bytes(ok) > 4096 * 2 * 1536 * 2 * 2
+    assert B.index_scratch_bytes(ok) >= 8 * 4
+    f32 = B.make_shape(7, 5, 3, 2, 1, "f32")            # fp32 takes any positive sizes
+    assert B.workspace_bytes(f32) > 0
+    for bad in (B.make_shape(0, 64, 64, 4, 1, "bf16"), B.make_shape(8, 64, 64, 0, 1, "bf16"),
+                B.make_shape(8, 64, 64, 4, 0, "bf16"), B.make_shape(8, -64, 64, 4, 1, "bf16"),
+                B.make_shape(8, 64, 64, 2000, 1, "bf16"),          # E > 1024
+                B.make_shape(2 ** 30, 64, 64, 4, 4, "bf16"),       # T*k overflows int32
+                B.make_shape(8, 60, 64, 4, 1, "bf16"),             # bf16 needs multiples of 64
+                B.Shape(8, 64, 64, 4, 1, 7)):                      # unknown dtype
+        assert B.workspace_bytes(bad) == 0 and B.index_scratch_bytes(bad) == 0
+
+
+def test_error_codes_without_touching_a_gpu(B):
+    lib = B.lib
+    ok = B.make_shape(8, 64, 64, 4, 1, "bf16")
+    none = B.Idx()
+    P = ctypes.c_void_p
+    assert lib.hexa_moe_index(None, None, none, None, 0, None) == 1                      # NULL shape
+    assert lib.hexa_moe_index(ctypes.byref(ok), None, none, None, 0, None) == 1          # NULL pointers
+    bad = B.make_shape(8, 60, 64, 4, 1, "bf16")
+    assert lib.hexa_moe_index(ctypes.byref(bad), None, none, None, 0, None) == 3         # unsupported
+    neg = B.make_shape(-1, 64, 64, 4, 1, "bf16")
+    assert lib.hexa_moe_index(ctypes.byref(neg), None, none, None, 0, None) == 2         # shape
+    fake = P(4096)   # never dereferenced: the size check fails first
+    idx = B.Idx(fake, fake, fake, fake)
+    assert lib.hexa_moe_index(ctypes.byref(ok), fake, idx, fake, 0, None) == 4           # scratch too small
+    assert lib.hexa_moe_fwd(ctypes.byref(ok), fake, fake, fake, fake, fake, fake, fake, idx, fake,
+                            fake, 16, None) == 4                                         # workspace too small
+    assert lib.hexa_moe_bwd(ctypes.byref(ok), fake, fake, fake, fake, fake, fake, idx, fake, 16, fake,
+                            fake, fake, fake, fake, None, None) == 4
+    assert lib.hexa_moe_fwd(ctypes.byref(ok), None, fake, fake, fake, fake, fake, fake, idx, fake,
+                            fake, 1 << 40, None) == 1
+    for code in range(6):
+        assert lib.hexa_moe_status_string(code)
+    assert b"unknown" in lib.hexa_moe_status_string(99)
+
+
+def test_binding_checks_tensor_shapes_on_the_host(B):
+    import torch
+    shape = B.make_shape(8, 64, 64, 4, 1, "bf16")
+    with pytest.raises(ValueError):
+        B._ptr(torch.zeros(8, 64), (8, 64), torch.bfloat16, "x")     # not a device tensor
+    with pytest.raises(B.HexaError) as ei:
+        B._check(3)
+    assert ei.value.code == 3
