@@ -25,9 +25,13 @@ sys.path.insert(0, ROOT)
 BF16_MFMA_PEAK_TFLOPS = 2500.0
 METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
 GEMM_LABELS = ("fc1", "fc2", "dgrad2", "dgrad1", "wgrad2", "wgrad1")
+# HBM-side bytes per launch at C5 from rocprofv3 (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 after calibration
+# with a plain 1 GiB copy; profiles/c5_gemm_pmc_counters.md).  Only meaningful for --workload C5.
+TRAFFIC_BYTES = {"fc1": 26.6e9, "fc2": 21.4e9, "dgrad2": 27.1e9, "dgrad1": 23.4e9, "wgrad2": 17.2e9,
+                 "wgrad1": 17.8e9}
 
 
-def cpu_baseline(w, data, sample_tokens=64, col_frac=16):
+def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
     """Oracle (fp64 loop nest) timed on the first `sample_tokens` tokens of the batch with all
     experts resident; the per-expert gradients on f/col_frac of the hidden units (each hidden
     unit is an independent, equal share of that work).  Returns useful TFLOP/s per the same
@@ -68,6 +72,8 @@ def main():
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--routing", default=None, help="override the routing recipe (zipf, forced, ...)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (all experts resident, no collectives); "
@@ -96,6 +102,12 @@ def main():
         grads = B.hexa_moe_bwd(shape, data["dY"], data["x"], data["topk_idx"], data["gate"],
                                data["W1"], data["W2"], idx, ws, out=grads)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -128,7 +140,7 @@ def main():
                    "tokens_per_expert": {"min": int(counts.min()), "max": int(counts.max())}},
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16<{dom}>", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom) if w.name == "C5" and not args.routing else None,
                      "flop_per_launch": gemm_flop, "avg_ms": kernels[dom]["ms"]},
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
     }

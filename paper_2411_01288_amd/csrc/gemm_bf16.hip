@@ -124,7 +124,10 @@ __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uin
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
         (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds);
     soff = __builtin_amdgcn_readfirstlane(soff);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+#ifndef HEXA_DTL_AUX
+#define HEXA_DTL_AUX ""
+#endif
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen" HEXA_DTL_AUX " lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(r), "s"(soff)
                  : "memory");
@@ -556,52 +559,119 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #undef ISSUE_A
 #undef ISSUE_B
 
-    // ---- epilogue: in block (i, j) a lane holds row i*32 + l32 and, in register quad q, the four
-    // columns j*32 + 8q + 4hi + 0..3 -------------------------------------------------------------
-    const size_t ldo = (size_t)g.N;
+    // ---- epilogue ------------------------------------------------------------------------------
+    // In block (i, j) a lane holds row i*32 + l32 and, in register quad q, the four columns
+    // j*32 + 8q + 4hi + 0..3.  Stored from there, a wave instruction would touch 32 rows with 8 or
+    // 16 bytes each.  Instead each wave turns one 32-row band (i) at a time through its own 32 KB
+    // of the (now idle) stage ring: vectors are written at [row][chunk ^ row] (16-byte chunks, so
+    // both directions are conflict-free), read back with a lane per 16-byte chunk of a row, and
+    // leave as full 256- or 512-byte row segments.  DGRAD2's saved pre-activations come in the
+    // same way, staged one band ahead.
+    __syncthreads();   // every wave is done reading fragments
+    {
+        uint8_t* wreg = smem + uwave * 32768;
+        constexpr bool OUT_F32 = TOKENS || OP == OP_FC2 || OP == OP_DGRAD1;
+        constexpr int ESZ = OUT_F32 ? 4 : 2;
+        constexpr int RPB = TN * ESZ;                 // bytes per staged row (TN columns)
+        constexpr int CPRO = RPB / 16;                // 16-byte chunks per staged row
+        static_assert(TN == 128, "epilogue staging is laid out for 128-column wave tiles");
+        const size_t ldo = (size_t)g.N;
+        const int wrow0 = wm * TM, wcol0 = wn * TN;
+        // DGRAD2: stage pre[band][128 cols] (bf16, 256 B rows, chunk ^ (row & 15)) with direct loads
+        rsrc_t rp;
+        uint32_t pre_voff = 0;
+        if constexpr (OP == OP_DGRAD2) {
+            rp = make_rsrc(g.pre_in + (size_t)m0 * ldo, (uint32_t)mvalid * (uint32_t)ldo * 2u);
+            const int prow = lane >> 4, ppos = lane & 15;          // instr t covers rows 4t..4t+3
+            pre_voff = (uint32_t)((wrow0 + prow) * (int)ldo + n0 + wcol0) * 2u;
+            (void)ppos;
+        }
+        auto stage_pre = [&](int band, int buf) {
+            if constexpr (OP == OP_DGRAD2) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int row = wm * TM + i * 32 + l32;
-        const bool rok = row < mvalid;
-        const size_t orow = (size_t)(m0 + row) * ldo + (size_t)n0;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = wn * TN + j * 32 + 8 * q + 4 * hi;
-#ifdef HEXA_DBG_NOEPI
-                if (acc[i][j][4 * q] != 12345.f) continue;
-#endif
-                if (!rok || col >= nvalid) continue;
-                float v[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
-                if constexpr (OP == OP_FC1 || OP == OP_FC2) {
-                    const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + n0 + col);
-                    v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
-                    v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                for (int t = 0; t < 8; ++t) {
+                    const int row = 4 * t + (lane >> 4);
+                    const int c = (lane & 15) ^ (row & 15);
+                    dtl16(rp, wreg + 16384 + buf * 8192 + t * 1024,
+                          pre_voff + (uint32_t)((band * 32 + 4 * t) * (int)ldo + c * 8) * 2u, 0u);
                 }
-                const size_t oi = orow + col;
-                if constexpr (TOKENS) {
-                    *reinterpret_cast<float4*>(tok_out + oi) = make_float4(v[0], v[1], v[2], v[3]);
-                } else if constexpr (OP == OP_FC1) {
-                    u32x2 p, h;
-                    p.x = pack_bf2(v[0], v[1]); p.y = pack_bf2(v[2], v[3]);
-                    h.x = pack_bf2(gelu_fast(v[0]), gelu_fast(v[1]));
-                    h.y = pack_bf2(gelu_fast(v[2]), gelu_fast(v[3]));
-                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = p;
-                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out1) + oi) = h;
+            }
+        };
+        stage_pre(0, 0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            if constexpr (OP == OP_DGRAD2) {
+                if (i + 1 < FM) stage_pre(i + 1, (i + 1) & 1);
+                if (i + 1 < FM) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            // -- registers -> LDS band
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = j * 32 + 8 * q + 4 * hi;       // column inside the wave tile
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
+                    if constexpr (OP == OP_FC1 || OP == OP_FC2) {
+                        const int gc = min(n0 + wcol0 + col, g.N - 4);   // masked columns read a valid bias
+                        const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
+                        v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
+                        v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                    }
+                    if constexpr (OUT_F32) {
+                        const int c = col >> 2;
+                        *reinterpret_cast<float4*>(wreg + l32 * RPB + ((c ^ (l32 & (CPRO - 1))) << 4)) =
+                            make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        const int c = col >> 3;
+                        const uint32_t off = (uint32_t)(l32 * RPB + ((c ^ (l32 & (CPRO - 1))) << 4) + hi * 8);
+                        if constexpr (OP == OP_FC1) {
+                            u32x2 pz, hz;
+                            pz.x = pack_bf2(v[0], v[1]); pz.y = pack_bf2(v[2], v[3]);
+                            hz.x = pack_bf2(gelu_fast(v[0]), gelu_fast(v[1]));
+                            hz.y = pack_bf2(gelu_fast(v[2]), gelu_fast(v[3]));
+                            *reinterpret_cast<u32x2*>(wreg + off) = pz;
+                            *reinterpret_cast<u32x2*>(wreg + 8192 + off) = hz;
+                        } else {   // DGRAD2
+                            const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + 16384 + (i & 1) * 8192 + off);
+                            const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
+                            const float p2 = __uint_as_float(pp.y << 16), p3 = __uint_as_float(pp.y & 0xffff0000u);
+                            u32x2 d;
+                            d.x = pack_bf2(v[0] * gelu_grad_fast(p0), v[1] * gelu_grad_fast(p1));
+                            d.y = pack_bf2(v[2] * gelu_grad_fast(p2), v[3] * gelu_grad_fast(p3));
+                            *reinterpret_cast<u32x2*>(wreg + off) = d;
+                        }
+                    }
+                }
+            }
+            // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
+            constexpr int RPI_O = 1024 / RPB;            // rows per instruction
+#pragma unroll
+            for (int t = 0; t < 32 / RPI_O; ++t) {
+                const int row = RPI_O * t + lane / CPRO;
+                const int c = (lane % CPRO) ^ (row & (CPRO - 1));
+                const int col = wcol0 + c * (16 / ESZ);
+                const int trow = wrow0 + i * 32 + row;
+#ifdef HEXA_DBG_NOEPI
+                if (acc[i][0][t % 16] != 12345.f) continue;
+#endif
+                const bool ok = trow < mvalid && col < nvalid;
+                const size_t oi = (size_t)(m0 + trow) * ldo + (size_t)(n0 + col);
+                const u32x4 d0 = *reinterpret_cast<const u32x4*>(wreg + t * 1024 + lane * 16);
+                if constexpr (OP == OP_FC1) {
+                    const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + 8192 + t * 1024 + lane * 16);
+                    if (ok) {
+                        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d0;
+                        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out1) + oi) = d1;
+                    }
                 } else if constexpr (OP == OP_DGRAD2) {
-                    const u32x2 pp = *reinterpret_cast<const u32x2*>(g.pre_in + oi);
-                    const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
-                    const float p2 = __uint_as_float(pp.y << 16), p3 = __uint_as_float(pp.y & 0xffff0000u);
-                    u32x2 d;
-                    d.x = pack_bf2(v[0] * gelu_grad_fast(p0), v[1] * gelu_grad_fast(p1));
-                    d.y = pack_bf2(v[2] * gelu_grad_fast(p2), v[3] * gelu_grad_fast(p3));
-                    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d;
+                    if (ok) *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d0;
+                } else if constexpr (TOKENS) {
+                    if (ok) *reinterpret_cast<u32x4*>(tok_out + oi) = d0;
                 } else {
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.out0) + oi) =
-                        make_float4(v[0], v[1], v[2], v[3]);
+                    if (ok) *reinterpret_cast<u32x4*>(reinterpret_cast<float*>(g.out0) + oi) = d0;
                 }
             }
         }
