@@ -65,7 +65,7 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
     w.dout = take(A * d * es);
     w.dpre = take(A * f * es);
     w.dxp = (float*)take(A * d * 4);
-    w.colpart = (float*)take((A / 128 + D.E) * (d > f ? d : f) * 4);
+    w.colpart = (float*)take((A / 128 + 2 * (size_t)D.E) * (d > f ? d : f) * 4);
     if (dtype == HEXA_BF16) {
         w.xg = take(A * d * es);
         w.kpart_slots = wgrad_max_slots(D);
@@ -209,7 +209,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
             e = launch_bf16_bwd(D, (const bf16_t*)ws.xg, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
                                 dW1, dW2, st);
         if (e == hipSuccess)
-            e = launch_segment_colsum<bf16_t>(D, (const bf16_t*)ws.dpre, D.f, idx.offsets, ws.colpart, db1, st);
+            e = launch_tile_colsum_finish(D, ws.colpart, D.f, idx.offsets, db1, st);
         if (e == hipSuccess) e = launch_combine_dx<bf16_t>(D, ws.dxp, idx.inv, (bf16_t*)dx, st);
     }
     return dev(e);

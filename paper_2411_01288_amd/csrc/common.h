@@ -88,12 +88,14 @@ struct MoeWorkspace {
     void* dpre;     // [A,f] elem                                       (bwd staging)
     float* dxp;     // [A,d] f32    per-assignment input gradients     (bwd staging)
     void* xg;       // [A,d] elem   x gathered to perm order (bf16 path)(bwd staging)
-    float* colpart; // [A/128+E, max(d,f)] f32 partial column sums     (bwd staging)
+    float* colpart; // [A/128+2E, max(d,f)] f32 partial column sums    (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
     size_t kpart_slots;
     size_t total_bytes;
 };
 
+int gemm_row_tile();                 // rows of a bf16 row-GEMM tile
+int gemm_colpart_rows_per_tile();    // DGRAD2 writes this many column-sum partial rows per row tile
 int wgrad_chunk_len(const MoeDims& D);          // tokens per split-K chunk (host policy)
 size_t wgrad_max_slots(const MoeDims& D);
 
@@ -116,6 +118,11 @@ hipError_t launch_combine_dx(const MoeDims& D, const float* dxp, const int32_t* 
 template <typename T>
 hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, const int32_t* offsets,
                                  float* partial, float* out, hipStream_t st);
+
+// second stage for column sums the bf16 DGRAD2 kernel left per (row tile, wave row):
+// out[e][c] = sum of the partial rows of the expert's tiles, in tile order
+hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int ncols,
+                                     const int32_t* offsets, float* out, hipStream_t st);
 
 // fp32 reference-precision path (plain FMA tiles)
 hipError_t launch_f32_fwd(const MoeDims& D, const float* x, const float* W1, const float* b1,

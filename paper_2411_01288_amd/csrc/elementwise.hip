@@ -187,6 +187,23 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ p
     out[(size_t)e * ncols + c] = acc;
 }
 
+// out[e][c] = sum over the expert's row tiles (tile height bm, `parts` partial rows per tile) of
+// partial[tile*parts + q][c], in order; exact 0 for an expert without rows.
+__global__ __launch_bounds__(256) void tile_colsum_finish(const float* __restrict__ partial, int ncols,
+                                                          int E, int bm, int parts,
+                                                          const int32_t* __restrict__ offsets,
+                                                          float* __restrict__ out) {
+    const int e = blockIdx.x;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= ncols) return;
+    int first = 0;
+    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], bm);
+    const int nt = ceil_div(offsets[e + 1] - offsets[e], bm);
+    float acc = 0.f;
+    for (int i = 0; i < nt * parts; ++i) acc += partial[(size_t)(first * parts + i) * ncols + c];
+    out[(size_t)e * ncols + c] = acc;
+}
+
 template <typename T>
 hipError_t combine_impl(int T_, int d, int k, const float* src, const int32_t* inv,
                         const float* gate, T* dst, hipStream_t st) {
@@ -242,6 +259,14 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
                        offsets, partial);
     hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, offsets,
                        out);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int ncols,
+                                     const int32_t* offsets, float* out, hipStream_t st) {
+    ProfScope ps(st, "colsum_db1");
+    hipLaunchKernelGGL(tile_colsum_finish, dim3(D.E, ceil_div(ncols, 256)), dim3(256), 0, st, partial, ncols,
+                       D.E, gemm_row_tile(), gemm_colpart_rows_per_tile(), offsets, out);
     return hipGetLastError();
 }
 

@@ -32,7 +32,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 32;           // contraction elements per LDS stage
+#ifndef HEXA_BK
+#define HEXA_BK 32
+#endif
+constexpr int BK = HEXA_BK;           // contraction elements per LDS stage
 #ifndef HEXA_NS
 #define HEXA_NS 4
 #endif
@@ -53,6 +56,7 @@ struct GemmArgs {
     void* out0;
     void* out1;
     float* kpart;         // split-K slots [slot][M][N]
+    float* colpart;       // DGRAD2: per (row tile, wave row) column sums of dpre [2*tiles][N]
     int topk, E, K, N, M;
     int a_rows;           // FC1: rows of the gathered operand (tokens T)
     int chunk_len;        // token contraction: max tokens per work item
@@ -124,10 +128,7 @@ __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uin
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
         (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds);
     soff = __builtin_amdgcn_readfirstlane(soff);
-#ifndef HEXA_DTL_AUX
-#define HEXA_DTL_AUX ""
-#endif
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen" HEXA_DTL_AUX " lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(r), "s"(soff)
                  : "memory");
@@ -184,18 +185,6 @@ struct StageKS {
 // ---------------------------------------------------------------------------------------------
 // Work decomposition
 // ---------------------------------------------------------------------------------------------
-
-// XCD-aware id: the G logical items are cut into 8 contiguous ranges, one per XCD.
-__device__ __forceinline__ int xcd_remap(int wg, int G) {
-#ifdef HEXA_DBG_NOXCD
-    return wg < G ? wg : -1;
-#endif
-    const int per = ceil_div(G, kXcds);
-    const int xcd = wg % kXcds, loc = wg / kXcds;
-    if (loc >= per) return -1;
-    const int pid = xcd * per + loc;
-    return pid < G ? pid : -1;
-}
 
 // Inside one set of tm x tn tiles: groups of kGroupM row tiles, row tile fastest inside a group.
 __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& tile_m, int& tile_n) {
@@ -256,28 +245,29 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 
     // ---- which work item ------------------------------------------------------------------
     int e, m0, n0, mvalid, nk;
+    int row_tile = 0;                 // row GEMMs: number of this row tile over all segments
     int kbeg = 0, kend = 0;           // token contraction: perm rows of this item
     float* tok_out = nullptr;         // token contraction: where the tile goes
     if constexpr (!TOKENS) {
-#ifdef HEXA_DBG_UNIFORM
-        const int tm_total = 1024;
-#else
         const int tm_total = seg_tiles_total(g.offsets, g.E, BM);
-#endif
         const int tn = ceil_div(g.N, BN);
-        const int pid = xcd_remap(blockIdx.x, tm_total * tn);
-        if (pid < 0) return;
         int tile_m, tile_n;
-        grouped_tile(pid, tm_total, tn, tile_m, tile_n);
-#ifdef HEXA_DBG_SAMETILE
-        tile_m = HEXA_DBG_SAMETILE == 1 ? 0 : (tile_m % HEXA_DBG_SAMETILE); tile_n = HEXA_DBG_SAMETILE == 1 ? 0 : tile_n;
-#endif
-#ifdef HEXA_DBG_UNIFORM
-        const SegTile s{tile_m / 16, tile_m * 256, 256};
-#else
+        {   // groups of kGroupM row tiles x all column tiles are dealt round-robin to the XCDs, so
+            // the 8 XCDs work on neighbouring row tiles (mostly one expert) at any time
+            const int per_group = kGroupM * tn;
+            const int ngroups = ceil_div(tm_total, kGroupM);
+            const int xcd = blockIdx.x % kXcds, loc = blockIdx.x / kXcds;
+            const int group = (loc / per_group) * kXcds + xcd;
+            const int within = loc % per_group;
+            if (group >= ngroups) return;
+            const int first = group * kGroupM;
+            const int gsz = min(kGroupM, tm_total - first);
+            if (within >= gsz * tn) return;
+            tile_m = first + within % gsz;
+            tile_n = within / gsz;
+        }
         const SegTile s = seg_tile_find(g.offsets, g.E, BM, tile_m);
-#endif
-        e = s.e; m0 = s.row0; mvalid = s.rows; n0 = tile_n * BN;
+        e = s.e; m0 = s.row0; mvalid = s.rows; n0 = tile_n * BN; row_tile = tile_m;
         nk = g.K / BK;
     } else {
         // every (expert, chunk) item is a set of tm*tn tiles over the same tokens; each XCD takes
@@ -299,12 +289,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     }
     const int nvalid = min(BN, g.N - n0);
 
-#ifndef HEXA_DBG_PADA
-#define HEXA_DBG_PADA 0
-#endif
-#ifndef HEXA_DBG_PADB
-#define HEXA_DBG_PADB 0
-#endif
     // ---- staging set-up -----------------------------------------------------------------------
     constexpr int NW = WM * WN;
     using SA = typename std::conditional<TOKENS, StageKS<BM, NW>, StageKC<BM, NW>>::type;
@@ -319,14 +303,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
         // FC1 gathers token rows of x through the re-index vector; the other row GEMMs read
         // perm-ordered rows, and rows past the segment fall outside the resource (zeros)
         if constexpr (OP == OP_FC1) ra = make_rsrc(g.A, (uint32_t)g.a_rows * (uint32_t)g.K * 2u);
-        else ra = make_rsrc(g.A + (size_t)m0 * (g.K + HEXA_DBG_PADA), (uint32_t)mvalid * (uint32_t)(g.K + HEXA_DBG_PADA) * 2u);
+        else ra = make_rsrc(g.A + (size_t)m0 * g.K, (uint32_t)mvalid * (uint32_t)g.K * 2u);
         a_step = BK * 2;
         const uint32_t ca = (uint32_t)SA::lane_chunk(uwave, lane) * 16u;
 #pragma unroll
         for (int i = 0; i < SA::NI; ++i) {
             uint32_t r = (uint32_t)SA::lane_row(uwave, lane, i);
             if constexpr (OP == OP_FC1) r = (uint32_t)(g.perm[m0 + ((int)r < mvalid ? (int)r : 0)] / g.topk);
-            lna.voff[i] = r * (uint32_t)(g.K + HEXA_DBG_PADA) * 2u + ca;
+            lna.voff[i] = r * (uint32_t)g.K * 2u + ca;
         }
         if constexpr (B_KS) {  // W[e][K][N]
             b_ld = (uint32_t)g.N * 2u;
@@ -334,12 +318,12 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             b_step = BK * b_ld;
             lnb = SB::lane_init(uwave, lane, b_ld, n0);
         } else {               // W[e][N][K]: rows past N fall outside the resource
-            rb = make_rsrc(g.B + ((size_t)e * g.N + n0) * (g.K + HEXA_DBG_PADB), (uint32_t)nvalid * (uint32_t)(g.K + HEXA_DBG_PADB) * 2u);
+            rb = make_rsrc(g.B + ((size_t)e * g.N + n0) * g.K, (uint32_t)nvalid * (uint32_t)g.K * 2u);
             b_step = BK * 2;
             const uint32_t cb = (uint32_t)SB::lane_chunk(uwave, lane) * 16u;
 #pragma unroll
             for (int i = 0; i < SB::NI; ++i)
-                lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)(g.K + HEXA_DBG_PADB) * 2u + cb;
+                lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)g.K * 2u + cb;
         }
     } else {
         // both operands are [tokens][features] in perm order; tokens past this item's range fall
@@ -506,7 +490,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             _Pragma("unroll") for (int o = 0; o < ND; ++o) ISSUE_ANY(buf, kj, o);
         }
     }
-    WAIT_STAGE();
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ND * (NS - 2)) : "memory");
     __syncthreads();
     _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa0, fb0, smem, 0, m);
 #ifdef HEXA_DBG_NOREAD
@@ -598,6 +582,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             }
         };
         stage_pre(0, 0);
+        float cs0 = 0.f, cs1 = 0.f;   // DGRAD2: sums of columns 2*lane, 2*lane+1 over this wave's rows (ESS, Table 5 row 8)
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             if constexpr (OP == OP_DGRAD2) {
@@ -646,6 +631,17 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                     }
                 }
             }
+            if constexpr (OP == OP_DGRAD2) {
+                // bias-gradient partial: the band holds the rounded dpre values the weight gradient
+                // will read; rows past the segment and columns past N are exact zeros
+#pragma unroll 8
+                for (int row = 0; row < 32; ++row) {
+                    const uint32_t w2 = *reinterpret_cast<const uint32_t*>(
+                        wreg + row * RPB + ((((lane >> 2) ^ (row & 15))) << 4) + (lane & 3) * 4);
+                    cs0 += __uint_as_float(w2 << 16);
+                    cs1 += __uint_as_float(w2 & 0xffff0000u);
+                }
+            }
             // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
             constexpr int RPI_O = 1024 / RPB;            // rows per instruction
 #pragma unroll
@@ -674,6 +670,12 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                     if (ok) *reinterpret_cast<u32x4*>(reinterpret_cast<float*>(g.out0) + oi) = d0;
                 }
             }
+        }
+        if constexpr (OP == OP_DGRAD2) {
+            const int col = wcol0 + 2 * lane;
+            if (col < nvalid)
+                *reinterpret_cast<float2*>(g.colpart + (size_t)(row_tile * WM + wm) * ldo + n0 + col) =
+                    make_float2(cs0, cs1);
         }
     }
 }
@@ -719,8 +721,7 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char
         attr_done = true;
     }
     const int tm_max = D.A / BM + D.E;
-    const int gmax = tm_max * ceil_div(g.N, BN);
-    const int grid = kXcds * ceil_div(gmax, kXcds);
+    const int grid = kXcds * ceil_div(ceil_div(tm_max, kGroupM), kXcds) * kGroupM * ceil_div(g.N, BN);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
 }
 
@@ -752,6 +753,10 @@ void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st, const ch
 constexpr int TBM = 256, TBN = 256, TWM = 2, TWN = 2;
 
 }  // namespace
+
+// Row-tile height and partial rows per tile of the DGRAD2 column-sum partials (for the finisher).
+int gemm_row_tile() { return TBM; }
+int gemm_colpart_rows_per_tile() { return TWM; }
 
 // Tokens per split-K chunk of the token contractions: long enough that most experts are one
 // chunk (no partial traffic), short enough that ~4 items per CU exist under skewed routing.
@@ -792,6 +797,7 @@ hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
     // dpre = (do W2^T) * GELU'(pre)
     g.A = (const bf16_t*)ws.dout; g.B = W2; g.pre_in = (const bf16_t*)ws.pre; g.out0 = ws.dpre;
+    g.colpart = ws.colpart;
     g.K = D.d; g.N = D.f;
     launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD2>(D, g, st, "dgrad2");
     // dW2[e] = h^T do
