@@ -311,6 +311,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             uint32_t r = (uint32_t)SA::lane_row(uwave, lane, i);
             if constexpr (OP == OP_FC1) r = (uint32_t)(g.perm[m0 + ((int)r < mvalid ? (int)r : 0)] / g.topk);
             lna.voff[i] = r * (uint32_t)g.K * 2u + ca;
+#ifdef HEXA_DBG_FULLLINE
+            lna.voff[i] = (uint32_t)(16 * (uwave + NW * i) + lane / 8) * (uint32_t)g.K * 2u + (uint32_t)(lane % 8) * 16u;
+#endif
         }
         if constexpr (B_KS) {  // W[e][K][N]
             b_ld = (uint32_t)g.N * 2u;
@@ -324,6 +327,11 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #pragma unroll
             for (int i = 0; i < SB::NI; ++i)
                 lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)g.K * 2u + cb;
+#ifdef HEXA_DBG_FULLLINE
+#pragma unroll
+            for (int i = 0; i < SB::NI; ++i)
+                lnb.voff[i] = (uint32_t)(16 * (uwave + NW * i) + lane / 8) * (uint32_t)g.K * 2u + (uint32_t)(lane % 8) * 16u;
+#endif
         }
     } else {
         // both operands are [tokens][features] in perm order; tokens past this item's range fall
@@ -337,16 +345,21 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             lnb = SB::lane_init(uwave, lane, b_ld, n0);
         }
     }
+#ifdef HEXA_DBG_FULLLINE
+#define KOFF(kt_, st_) ((((kt_) >> 1) * 128u) + ((kt_) & 1u) * 8u * (uint32_t)g.K * 2u)
+#else
+#define KOFF(kt_, st_) ((kt_) * (st_))
+#endif
     // one staging instruction of operand A / B for K-step kt_ into LDS stage buffer buf_
 #define ISSUE_A(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
         if constexpr (TOKENS) SA::issue(ra, (buf_), uwave, a_ld, (kt_) * a_step, lna, i_);       \
-        else SA::issue(ra, (buf_), uwave, (kt_) * a_step, lna, i_);                              \
+        else SA::issue(ra, (buf_), uwave, KOFF(kt_, a_step), lna, i_);                              \
     } while (0)
 #define ISSUE_B(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
         if constexpr (B_KS) SB::issue(rb, (buf_) + BM * ROWB, uwave, b_ld, (kt_) * b_step, lnb, i_); \
-        else SB::issue(rb, (buf_) + BM * ROWB, uwave, (kt_) * b_step, lnb, i_);                   \
+        else SB::issue(rb, (buf_) + BM * ROWB, uwave, KOFF(kt_, b_step), lnb, i_);                   \
     } while (0)
 
     f32x16 acc[FM][FN];
@@ -444,7 +457,12 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     constexpr int NM = FM * FN;   // MFMAs per k-substep and wave
     static_assert(NRD <= NM, "fragment reads must fit the substep");
     constexpr int ND = SA::NI + SB::NI;          // staging instructions per wave and stage
-    constexpr int TS = (SPS - 1) * NM;           // slots they are spread over (all but the last substep)
+#ifndef HEXA_ISS
+#define HEXA_ISS (SPS - 1)
+#endif
+    constexpr int ISS = HEXA_ISS;                // substeps the staging instructions are spread over
+    constexpr int TS = ISS * NM;                 // slots they are spread over (never the last substep)
+    static_assert(ISS >= 1 && ISS <= SPS - 1, "staging issue window");
     // staging instruction number o_ of the next stage: A's first, then B's
 #define ISSUE_ANY(buf_, kt_, o_)                                                                 \
     do {                                                                                         \
@@ -517,10 +535,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             if (ss + 1 < SPS) {
                 if ((ss & 1) == 0)
                     SUBSTEP(fa0, fb0, DBG_READ(READ_ONE(fa1, fb1, sbase, ss + 1, m)),
-                            DBG_LOAD(SPREAD(ss * NM + m, pbase, kreq)));
+                            DBG_LOAD(if (ss < ISS) SPREAD(ss * NM + m, pbase, kreq)));
                 else
                     SUBSTEP(fa1, fb1, DBG_READ(READ_ONE(fa0, fb0, sbase, ss + 1, m)),
-                            DBG_LOAD(SPREAD(ss * NM + m, pbase, kreq)));
+                            DBG_LOAD(if (ss < ISS) SPREAD(ss * NM + m, pbase, kreq)));
             } else {
                 WAIT_STAGE();
                 __syncthreads();
