@@ -14,13 +14,14 @@
 // expert's weights; rows are addressed through the re-index vector, so nothing is padded to a
 // capacity and nothing is dropped.  What is not: the 16x16x16 warp tiles, the per-expert serial
 // loop of Alg. 4 and the padded (-1) re-index vector.  Here a workgroup owns a 256x256 (or
-// 128-wide) tile, each 64-lane wavefront a grid of 32x32x16 bf16 MFMA blocks, operands are
-// staged through LDS as [row][64 k] with a 16-byte XOR swizzle (conflict-free 128-bit reads),
-// operands whose contraction index is the slow one in memory (weights in the forward GEMMs,
-// both operands of the token contractions) are transposed in registers on the way to LDS,
-// segments are tiled individually (ragged tails are masked, not padded), long segments of the
-// token contractions are split into chunks whose partial tiles are reduced in a fixed order,
-// and workgroup ids are remapped so that the 32 CUs of one XCD work on neighbouring tiles.
+// 128-wide) tile, each 64-lane wavefront a grid of 32x32x16 bf16 MFMA blocks, operands go from
+// global memory straight into LDS (no registers in between) as [row][64 k] with a 16-byte XOR
+// swizzle (conflict-free 128-bit reads); operands whose contraction index is the slow one in
+// memory (weights in the forward GEMMs, both operands of the token contractions) keep their
+// memory layout in LDS and are transposed by the LDS read instruction; segments are tiled
+// individually (ragged tails are masked, not padded), long segments of the token contractions
+// are split into chunks whose partial tiles are reduced in a fixed order, and workgroup ids are
+// remapped so that the 32 CUs of one XCD work on neighbouring tiles.
 #include <type_traits>
 
 #include "common.h"
@@ -32,14 +33,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-#ifndef HEXA_BK
-#define HEXA_BK 32
-#endif
-constexpr int BK = HEXA_BK;           // contraction elements per LDS stage
-#ifndef HEXA_NS
-#define HEXA_NS 4
-#endif
-constexpr int NS = HEXA_NS;            // LDS stage ring depth (NS-1 stages are in flight)
+constexpr int BK = 64;            // contraction elements per block of the K loop (one 128-byte line per row)
+constexpr int NSLOT = 5;          // LDS ring: five slots, each holds one operand's share of a block
 constexpr int kXcds = 8;         // workgroup i is dispatched to XCD i % 8
 constexpr int kGroupM = 8;       // row tiles per L2-sharing group
 
@@ -232,11 +227,11 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     constexpr int FM = TM / 32, FN = TN / 32;
     constexpr bool TOKENS = (OP == OP_WGRAD2 || OP == OP_WGRAD1);
     constexpr bool B_KS = TOKENS || OP == OP_FC1 || OP == OP_FC2;
-    constexpr int STAGE = (BM + BN) * ROWB;   // bytes of one LDS stage (A image, then B image)
-    constexpr int SPS = BK / 16;              // k-substeps (one MFMA k each) per stage
+    constexpr int SLOT = (BM > BN ? BM : BN) * ROWB;   // bytes of one ring slot (one operand, one block)
+    constexpr int SPS = BK / 16;              // k-substeps (one MFMA k each) per block
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of 32x32");
 
-    extern __shared__ __align__(1024) uint8_t smem[];   // two stage buffers
+    extern __shared__ __align__(1024) uint8_t smem[];   // the slot ring; reused by the epilogue
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -311,9 +306,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             uint32_t r = (uint32_t)SA::lane_row(uwave, lane, i);
             if constexpr (OP == OP_FC1) r = (uint32_t)(g.perm[m0 + ((int)r < mvalid ? (int)r : 0)] / g.topk);
             lna.voff[i] = r * (uint32_t)g.K * 2u + ca;
-#ifdef HEXA_DBG_FULLLINE
-            lna.voff[i] = (uint32_t)(16 * (uwave + NW * i) + lane / 8) * (uint32_t)g.K * 2u + (uint32_t)(lane % 8) * 16u;
-#endif
         }
         if constexpr (B_KS) {  // W[e][K][N]
             b_ld = (uint32_t)g.N * 2u;
@@ -327,11 +319,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #pragma unroll
             for (int i = 0; i < SB::NI; ++i)
                 lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)g.K * 2u + cb;
-#ifdef HEXA_DBG_FULLLINE
-#pragma unroll
-            for (int i = 0; i < SB::NI; ++i)
-                lnb.voff[i] = (uint32_t)(16 * (uwave + NW * i) + lane / 8) * (uint32_t)g.K * 2u + (uint32_t)(lane % 8) * 16u;
-#endif
         }
     } else {
         // both operands are [tokens][features] in perm order; tokens past this item's range fall
@@ -345,21 +332,16 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             lnb = SB::lane_init(uwave, lane, b_ld, n0);
         }
     }
-#ifdef HEXA_DBG_FULLLINE
-#define KOFF(kt_, st_) ((((kt_) >> 1) * 128u) + ((kt_) & 1u) * 8u * (uint32_t)g.K * 2u)
-#else
-#define KOFF(kt_, st_) ((kt_) * (st_))
-#endif
     // one staging instruction of operand A / B for K-step kt_ into LDS stage buffer buf_
 #define ISSUE_A(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
         if constexpr (TOKENS) SA::issue(ra, (buf_), uwave, a_ld, (kt_) * a_step, lna, i_);       \
-        else SA::issue(ra, (buf_), uwave, KOFF(kt_, a_step), lna, i_);                              \
+        else SA::issue(ra, (buf_), uwave, (kt_) * a_step, lna, i_);                              \
     } while (0)
 #define ISSUE_B(buf_, kt_, i_)                                                                   \
     do {                                                                                         \
-        if constexpr (B_KS) SB::issue(rb, (buf_) + BM * ROWB, uwave, b_ld, (kt_) * b_step, lnb, i_); \
-        else SB::issue(rb, (buf_) + BM * ROWB, uwave, KOFF(kt_, b_step), lnb, i_);                   \
+        if constexpr (B_KS) SB::issue(rb, (buf_), uwave, b_ld, (kt_) * b_step, lnb, i_); \
+        else SB::issue(rb, (buf_), uwave, (kt_) * b_step, lnb, i_);                   \
     } while (0)
 
     f32x16 acc[FM][FN];
@@ -393,14 +375,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                 aoff[s] = (uint32_t)((wm * TM + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
         }
         if constexpr (B_KS) {
-            b_ks = (uint32_t)(BM * ROWB + (8 * hi + krel) * B_RB + dlt * 16 + half8);
+            b_ks = (uint32_t)((8 * hi + krel) * B_RB + dlt * 16 + half8);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 boff[j] = (uint32_t)((((wn * TN) / 8 + 4 * j) ^ (krel << 2)) * 16);
         } else {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                boff[s] = (uint32_t)(BM * ROWB + (wn * TN + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
+                boff[s] = (uint32_t)((wn * TN + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
         }
     }
     static_assert(FM <= 4 && FN <= 4, "fragment offset tables hold four entries");
@@ -408,153 +390,125 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     // two fragment sets: set (s & 1) is multiplied while the other one is being read
     bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
-// timing-only ablation switches (never defined in the library build)
-#ifdef HEXA_DBG_NOGLOBAL
-#define DBG_LOAD(x)
-#else
-#define DBG_LOAD(x) x
-#endif
-#ifdef HEXA_DBG_NOMFMA
-#define DBG_MFMA(stmt_) if (m == 0 && tid == 1023) { stmt_; }
-#else
-#define DBG_MFMA(stmt_) stmt_
-#endif
-#ifdef HEXA_DBG_NOREAD
-#define DBG_READ(x)
-#else
-#define DBG_READ(x) x
-#endif
 #define TR_READ(p_) __builtin_bit_cast(s16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p_)))
     // LDS reads of one k-substep are numbered: A fragments first, then B fragments; a K-strided
     // fragment takes two reads (k-rows +0..3 and +4..7), a K-contiguous one takes one.
     constexpr int RA = TOKENS ? 2 : 1, RBn = B_KS ? 2 : 1;
     constexpr int NRD = FM * RA + FN * RBn;
     s16x4 tra[FM], trb[FN];   // first halves of K-strided fragments
-#define READ_ONE(fa, fb, base_, s_, m_)                                                          \
+    // read number m_ of k-substep s_ from the slots at ab_ (A image) and bb_ (B image)
+#define READ_ONE(fa, fb, ab_, bb_, s_, m_)                                                       \
     do {                                                                                         \
         if ((m_) < FM * RA) {                                                                    \
             const int i_ = (m_) / RA;                                                            \
             if constexpr (TOKENS) {                                                              \
-                const uint8_t* p_ = (base_) + a_ks + aoff[i_] + (16 * (s_) + 4 * ((m_) % RA)) * A_RB; \
+                const uint8_t* p_ = (ab_) + a_ks + aoff[i_] + (16 * (s_) + 4 * ((m_) % RA)) * A_RB; \
                 if ((m_) % RA == 0) tra[i_] = TR_READ(p_);                                       \
                 else fa[i_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(tra[i_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
             } else {                                                                             \
-                fa[i_] = *reinterpret_cast<const bf16x8*>((base_) + aoff[s_] + i_ * 32 * ROWB);   \
+                fa[i_] = *reinterpret_cast<const bf16x8*>((ab_) + aoff[s_] + i_ * 32 * ROWB);     \
             }                                                                                    \
         } else if ((m_) < NRD) {                                                                 \
             const int mb_ = (m_) - FM * RA;                                                      \
             const int j_ = mb_ / RBn;                                                            \
             if constexpr (B_KS) {                                                                \
-                const uint8_t* p_ = (base_) + b_ks + boff[j_] + (16 * (s_) + 4 * (mb_ % RBn)) * B_RB; \
+                const uint8_t* p_ = (bb_) + b_ks + boff[j_] + (16 * (s_) + 4 * (mb_ % RBn)) * B_RB; \
                 if (mb_ % RBn == 0) trb[j_] = TR_READ(p_);                                       \
                 else fb[j_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(trb[j_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
             } else {                                                                             \
-                fb[j_] = *reinterpret_cast<const bf16x8*>((base_) + boff[s_] + j_ * 32 * ROWB);   \
+                fb[j_] = *reinterpret_cast<const bf16x8*>((bb_) + boff[s_] + j_ * 32 * ROWB);     \
             }                                                                                    \
         }                                                                                        \
     } while (0)
 
     constexpr int NM = FM * FN;   // MFMAs per k-substep and wave
     static_assert(NRD <= NM, "fragment reads must fit the substep");
-    constexpr int ND = SA::NI + SB::NI;          // staging instructions per wave and stage
-#ifndef HEXA_ISS
-#define HEXA_ISS (SPS - 1)
-#endif
-    constexpr int ISS = HEXA_ISS;                // substeps the staging instructions are spread over
-    constexpr int TS = ISS * NM;                 // slots they are spread over (never the last substep)
-    static_assert(ISS >= 1 && ISS <= SPS - 1, "staging issue window");
-    // staging instruction number o_ of the next stage: A's first, then B's
-#define ISSUE_ANY(buf_, kt_, o_)                                                                 \
+    static_assert(SPS == 4, "the schedule below is written for four k-substeps per block");
+    constexpr int NIA = SA::NI, NIB = SB::NI;    // staging instructions per wave, operand and block
+    static_assert((2 * NM) % NIA == 0 && NM % NIB == 0, "staging instructions must divide the issue slots");
+    // staging instruction of A for global slot g_ (0 .. 2*NM-1, substeps 0 and 1): every (2*NM/NIA)-th slot
+#define ISSUE_A_AT(g_, buf_, kt_)                                                                \
     do {                                                                                         \
-        if ((o_) < SA::NI) ISSUE_A(buf_, kt_, (o_) < SA::NI ? (o_) : 0);                         \
-        else ISSUE_B(buf_, kt_, (o_) >= SA::NI ? (o_) - SA::NI : 0);                             \
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o)                                          \
+            if (o * (2 * NM / NIA) == (g_)) ISSUE_A(buf_, kt_, o);                               \
     } while (0)
-    // staging instructions of global slot g_ (0 .. TS-1): numbers [g*ND/TS, (g+1)*ND/TS)
-#define SPREAD(g_, buf_, kt_)                                                                    \
+    // staging instruction of B for slot m_ (0 .. NM-1, substep 3): every (NM/NIB)-th slot
+#define ISSUE_B_AT(m_, buf_, kt_)                                                                \
     do {                                                                                         \
-        _Pragma("unroll") for (int o = 0; o < ND; ++o)                                           \
-            if (o >= (g_) * ND / TS && o < ((g_) + 1) * ND / TS) ISSUE_ANY(buf_, kt_, o);        \
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o)                                          \
+            if (o * (NM / NIB) == (m_)) ISSUE_B(buf_, kt_, o);                                   \
     } while (0)
     // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
     // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
     // tile row (l32) and 4 consecutive tile columns per register quad, which the epilogue stores
     // as 8- or 16-byte vectors.
     // One k-substep: NM MFMAs on fragment set (fa, fb); after MFMA m, memory slot m is issued
-    // (one fragment read for the next substep, and a share of the staging instructions), so the
+    // (one fragment read for the next substep, and at most one staging instruction), so the
     // LDS and vector-memory queues are fed a little at a time while the matrix pipe stays busy:
     // one wavefront per SIMD has nobody else to hide a burst behind.
 #define SUBSTEP(fa, fb, READ_, EXTRA_)                                                           \
     do {                                                                                         \
         _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                         \
-            DBG_MFMA(acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(              \
-                fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0));                          \
+            acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                       \
+                fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0);                           \
             FENCE();                                                                             \
             READ_;                                                                               \
             EXTRA_;                                                                              \
             FENCE();                                                                             \
         }                                                                                        \
     } while (0)
-    // wait until at most the NS-2 youngest stages of this wave's staging loads are outstanding
-#define WAIT_STAGE() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ND * (NS - 2)) : "memory")
-    static_assert(ND * (NS - 2) <= 63, "vmcnt is a 6-bit counter");
+    static_assert(NIA + NIB <= 63, "vmcnt is a 6-bit counter");
 
-    // Ring of NS stage buffers: stage j lives in buffer j % NS.  Prologue: request stages 0..NS-2.
+    // The K loop runs in blocks of BK = 64 (four k-substeps): a row of a K-contiguous operand is
+    // then one whole 128-byte line per block, and the texture-address path, which pays per line
+    // touched, moves twice the bytes it would with 32-k stages.  One block of one operand (32 KB)
+    // is a ring slot; the five slots of the 160 KB LDS hold, in request order,
+    //     A(j) B(j) | A(j+1) B(j+1) A(j+2)       block j being multiplied | requested ahead
+    // i.e. half-block h (A(j): h = 2j, B(j): h = 2j+1) lives in slot h % 5.
+    // During block j: substeps 0-1 request A(j+2) into the slot B(j-1) left; before substep 3 the
+    // wave waits until only that request is outstanding (so A(j+1), B(j+1) are complete) and the
+    // barrier publishes them; every fragment read of block j has been issued by then, so substep 3
+    // requests B(j+2) into A(j)'s slot while it reads the first fragments of block j+1.  Past the
+    // last block the requests re-fetch the last block into slots nobody reads, which keeps the
+    // loop body free of branches.
     const int klast = nk > 0 ? nk - 1 : 0;
     if (nk > 0) {
-#pragma unroll
-        for (int j = 0; j < NS - 1; ++j) {
-            uint8_t* buf = smem + j * STAGE;
-            const uint32_t kj = (uint32_t)min(j, klast);
-            _Pragma("unroll") for (int o = 0; o < ND; ++o) ISSUE_ANY(buf, kj, o);
-        }
+        const uint32_t k1 = (uint32_t)min(1, klast);
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o) ISSUE_A(smem + 0 * SLOT, 0u, o);
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o) ISSUE_B(smem + 1 * SLOT, 0u, o);
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o) ISSUE_A(smem + 2 * SLOT, k1, o);
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o) ISSUE_B(smem + 3 * SLOT, k1, o);
     }
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ND * (NS - 2)) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA + NIB) : "memory");
     __syncthreads();
-    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa0, fb0, smem, 0, m);
-#ifdef HEXA_DBG_NOREAD
-    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa1, fb1, smem, 1, m);
-#endif
+    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, m);
 
-    // One K-step (stage kt, BK = SPS*16 contraction elements).  While buffer kt % NS is multiplied,
-    // stage kt+NS-1 is requested into buffer (kt-1) % NS, which nobody reads any more: its last
-    // fragment reads were issued before the barrier of K-step kt-1.  Before the last substep the
-    // wave waits for its share of stage kt+1 and the barrier publishes that stage, whose first
-    // fragments are then read during the last substep.  Past the last stage the requests re-fetch
-    // the last stage into buffers nobody reads, which keeps the loop body free of branches.
-    int cur = 0;                                  // kt % NS
-    for (int kt = 0; kt < nk; ++kt) {
-        uint8_t* sbase = smem + cur * STAGE;
-        const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
-        const int prv = (cur == 0) ? NS - 1 : cur - 1;
-        uint8_t* nbase = smem + nxt * STAGE;
-        uint8_t* pbase = smem + prv * STAGE;
-        const uint32_t kreq = (uint32_t)min(kt + NS - 1, klast);
+    int sa = 0, sb = 1;                           // slots of A(j), B(j)
+    for (int j = 0; j < nk; ++j) {
+        uint8_t* abase = smem + sa * SLOT;
+        uint8_t* bbase = smem + sb * SLOT;
+        const int sa1 = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
+        const int sb1 = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
+        const int sa2 = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
+        uint8_t* anext = smem + sa1 * SLOT;
+        uint8_t* bnext = smem + sb1 * SLOT;
+        uint8_t* a2 = smem + sa2 * SLOT;          // A(j+2): the slot of B(j-1)
+        const uint32_t kreq = (uint32_t)min(j + 2, klast);
         FENCE();
-#pragma unroll
-        for (int ss = 0; ss < SPS; ++ss) {
-            if (ss + 1 < SPS) {
-                if ((ss & 1) == 0)
-                    SUBSTEP(fa0, fb0, DBG_READ(READ_ONE(fa1, fb1, sbase, ss + 1, m)),
-                            DBG_LOAD(if (ss < ISS) SPREAD(ss * NM + m, pbase, kreq)));
-                else
-                    SUBSTEP(fa1, fb1, DBG_READ(READ_ONE(fa0, fb0, sbase, ss + 1, m)),
-                            DBG_LOAD(if (ss < ISS) SPREAD(ss * NM + m, pbase, kreq)));
-            } else {
-                WAIT_STAGE();
-                __syncthreads();
-                FENCE();
-                if ((ss & 1) == 0) SUBSTEP(fa0, fb0, DBG_READ(READ_ONE(fa1, fb1, nbase, 0, m)), (void)0);
-                else SUBSTEP(fa1, fb1, DBG_READ(READ_ONE(fa0, fb0, nbase, 0, m)), (void)0);
-            }
-        }
-        cur = nxt;
+        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, m), ISSUE_A_AT(m, a2, kreq));
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, abase, bbase, 2, m), ISSUE_A_AT(NM + m, a2, kreq));
+        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 3, m), (void)0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
+        __syncthreads();
+        FENCE();
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, m), ISSUE_B_AT(m, abase, kreq));
+        sa = sa1; sb = sb1;
     }
     // no staging write may still be in flight when the workgroup gives its LDS back
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#undef WAIT_STAGE
-#undef ISSUE_ANY
+#undef ISSUE_A_AT
+#undef ISSUE_B_AT
 #undef SUBSTEP
-#undef SPREAD
 #undef READ_ONE
 #undef TR_READ
 #undef FENCE
@@ -731,7 +685,7 @@ template <int BM, int BN, int WM, int WN, int OP>
 void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label) {
     ProfScope ps(st, label);
     auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
-    constexpr int lds = NS * (BM + BN) * ROWB;
+    constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -747,7 +701,7 @@ template <int BM, int BN, int WM, int WN, int OP>
 void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label,
                    const char* label_fin) {
     auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
-    constexpr int lds = NS * (BM + BN) * ROWB;
+    constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
