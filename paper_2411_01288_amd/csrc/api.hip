@@ -70,6 +70,7 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
         w.xg = take(A * d * es);
         w.kpart_slots = wgrad_max_slots(D);
         w.kpart = (float*)take(w.kpart_slots * d * f * 4);
+        w.worklist = (int32_t*)take(gemm_worklist_ints(D) * 4);
     }
     w.total_bytes = off;
     return w;

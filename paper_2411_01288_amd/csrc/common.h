@@ -91,6 +91,7 @@ struct MoeWorkspace {
     float* colpart; // [A/128+2E, max(d,f)] f32 partial column sums    (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
     size_t kpart_slots;
+    int32_t* worklist; // row tiles and token-contraction items of the bf16 kernels (rebuilt by fwd and bwd)
     size_t total_bytes;
 };
 
@@ -98,6 +99,7 @@ int gemm_row_tile();                 // rows of a bf16 row-GEMM tile
 int gemm_colpart_rows_per_tile();    // DGRAD2 writes this many column-sum partial rows per row tile
 int wgrad_chunk_len(const MoeDims& D);          // tokens per split-K chunk (host policy)
 size_t wgrad_max_slots(const MoeDims& D);
+size_t gemm_worklist_ints(const MoeDims& D);    // int32 entries of MoeWorkspace::worklist
 
 hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx out, void* scratch,
                         hipStream_t st);

@@ -55,6 +55,8 @@ struct GemmArgs {
     int topk, E, K, N, M;
     int a_rows;           // FC1: rows of the gathered operand (tokens T)
     int chunk_len;        // token contraction: max tokens per work item
+    const int32_t* worklist;  // see build_worklists
+    int rt_cap;           // row-tile capacity of the work list
 };
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
@@ -192,29 +194,47 @@ __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& til
     tile_n = in / gsz;
 }
 
-struct TokenItem { int e, kbeg, kend, tile_m, tile_n, nchunks, slot; };
-
-// Token-contraction items, numbered expert-major then chunk: item `ec` covers perm rows
-// [kbeg, kend) of one expert.  slot = index into the split-K partial buffer (only used when the
-// expert has more than one chunk).  e = -1 past the last item.
-__device__ __forceinline__ TokenItem token_item_find(const int32_t* __restrict__ offsets, int E,
-                                                     int L, int tm, int tn, int ec, int tile) {
-    TokenItem it{-1, 0, 0, 0, 0, 0, 0};
-    int acc = 0, slot = 0;
-    for (int e = 0; e < E; ++e) {
-        const int b = offsets[e], n = offsets[e + 1] - b;
-        const int nch = ceil_div(n, L);
-        if (ec < acc + nch) {
-            const int c = ec - acc;
-            it.e = e; it.nchunks = nch; it.slot = slot + c;
-            it.kbeg = b + c * L; it.kend = min(b + n, it.kbeg + L);
-            grouped_tile(tile, tm, tn, it.tile_m, it.tile_n);
-            return it;
-        }
-        acc += nch;
-        if (nch > 1) slot += nch;
+// Work lists, built once per forward / backward call from the segment offsets, so that a
+// workgroup finds its tile with two scalar loads instead of a walk over all experts (which cost a
+// 256x256 tile of a d = 2048 contraction about a tenth of its time, with the CU idle meanwhile).
+//   wl[0] = number of row tiles, wl[1] = number of token-contraction items, wl[2..3] unused
+//   wl[4 + 4 t ...]            row tile t:  expert, first perm row, rows (1..bm), unused
+//   wl[4 + 4 rt_cap + 4 i ...] item i:      expert, first perm row, end perm row, split-K slot
+// Row tiles are numbered expert-major (tiles never straddle experts; experts without rows have
+// none).  Items are numbered expert-major then chunk: item i covers at most L rows of one expert;
+// slot >= 0 numbers the partial tile buffer of an expert that was cut into several chunks, -1
+// means the expert is one chunk and its tile goes straight to the output.
+__global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restrict__ offsets, int E,
+                                                        int bm, int L, int32_t* __restrict__ wl,
+                                                        int rt_cap) {
+    __shared__ int s_t[1024], s_c[1024], s_s[1024];
+    const int e = threadIdx.x;
+    int b = 0, n = 0, nt = 0, nc = 0, ns = 0;
+    if (e < E) {
+        b = offsets[e]; n = offsets[e + 1] - b;
+        nt = ceil_div(n, bm); nc = ceil_div(n, L); ns = nc > 1 ? nc : 0;
     }
-    return it;
+    s_t[e] = nt; s_c[e] = nc; s_s[e] = ns;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {      // inclusive scans
+        int vt = 0, vc = 0, vs = 0;
+        if (e >= off) { vt = s_t[e - off]; vc = s_c[e - off]; vs = s_s[e - off]; }
+        __syncthreads();
+        s_t[e] += vt; s_c[e] += vc; s_s[e] += vs;
+        __syncthreads();
+    }
+    if (e >= E) return;
+    int t0 = s_t[e] - nt, c0 = s_c[e] - nc, slot0 = s_s[e] - ns;
+    for (int i = 0; i < nt; ++i) {
+        int32_t* q = wl + 4 + 4 * (t0 + i);
+        q[0] = e; q[1] = b + i * bm; q[2] = min(bm, n - i * bm); q[3] = 0;
+    }
+    int32_t* items = wl + 4 + 4 * rt_cap;
+    for (int c = 0; c < nc; ++c) {
+        int32_t* q = items + 4 * (c0 + c);
+        q[0] = e; q[1] = b + c * L; q[2] = min(b + n, b + c * L + L); q[3] = nc > 1 ? slot0 + c : -1;
+    }
+    if (e == E - 1) { wl[0] = s_t[e]; wl[1] = s_c[e]; wl[2] = 0; wl[3] = 0; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -244,7 +264,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     int kbeg = 0, kend = 0;           // token contraction: perm rows of this item
     float* tok_out = nullptr;         // token contraction: where the tile goes
     if constexpr (!TOKENS) {
-        const int tm_total = seg_tiles_total(g.offsets, g.E, BM);
+        const int tm_total = g.worklist[0];
         const int tn = ceil_div(g.N, BN);
         int tile_m, tile_n;
         {   // groups of kGroupM row tiles x all column tiles are dealt round-robin to the XCDs, so
@@ -261,8 +281,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             tile_m = first + within % gsz;
             tile_n = within / gsz;
         }
-        const SegTile s = seg_tile_find(g.offsets, g.E, BM, tile_m);
-        e = s.e; m0 = s.row0; mvalid = s.rows; n0 = tile_n * BN; row_tile = tile_m;
+        const i32x4 rt = *reinterpret_cast<const i32x4*>(g.worklist + 4 + 4 * tile_m);
+        e = rt.x; m0 = rt.y; mvalid = rt.z; n0 = tile_n * BN; row_tile = tile_m;
         nk = g.K / BK;
     } else {
         // every (expert, chunk) item is a set of tm*tn tiles over the same tokens; each XCD takes
@@ -274,13 +294,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
         const int xcd = blockIdx.x % kXcds, loc = blockIdx.x / kXcds;
         const int tile = xcd * per + loc % per;
         if (tile >= tmn) return;
-        const TokenItem it = token_item_find(g.offsets, g.E, g.chunk_len, tm, tn, loc / per, tile);
-        if (it.e < 0) return;
-        e = it.e; m0 = it.tile_m * BM; n0 = it.tile_n * BN; mvalid = min(BM, g.M - m0);
-        kbeg = it.kbeg; kend = it.kend;
+        if (loc / per >= g.worklist[1]) return;
+        const i32x4 it = *reinterpret_cast<const i32x4*>(g.worklist + 4 + 4 * g.rt_cap + 4 * (loc / per));
+        int tile_m, tile_n;
+        grouped_tile(tile, tm, tn, tile_m, tile_n);
+        e = it.x; m0 = tile_m * BM; n0 = tile_n * BN; mvalid = min(BM, g.M - m0);
+        kbeg = it.y; kend = it.z;
         nk = ceil_div(kend - kbeg, BK);
-        tok_out = (it.nchunks > 1) ? g.kpart + (size_t)it.slot * g.M * g.N
-                                   : reinterpret_cast<float*>(g.out0) + (size_t)e * g.M * g.N;
+        tok_out = (it.w >= 0) ? g.kpart + (size_t)it.w * g.M * g.N
+                              : reinterpret_cast<float*>(g.out0) + (size_t)e * g.M * g.N;
     }
     const int nvalid = min(BN, g.N - n0);
 
@@ -425,18 +447,19 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     static_assert(NRD <= NM, "fragment reads must fit the substep");
     static_assert(SPS == 4, "the schedule below is written for four k-substeps per block");
     constexpr int NIA = SA::NI, NIB = SB::NI;    // staging instructions per wave, operand and block
+    constexpr int ASTR = 2 * NM / NIA, BSTR = NM / NIB;   // issue-slot strides of the two operands
     static_assert((2 * NM) % NIA == 0 && NM % NIB == 0, "staging instructions must divide the issue slots");
     // staging instruction of A for global slot g_ (0 .. 2*NM-1, substeps 0 and 1): every (2*NM/NIA)-th slot
 #define ISSUE_A_AT(g_, buf_, kt_)                                                                \
     do {                                                                                         \
         _Pragma("unroll") for (int o = 0; o < NIA; ++o)                                          \
-            if (o * (2 * NM / NIA) == (g_)) ISSUE_A(buf_, kt_, o);                               \
+            if (o * ASTR == (g_)) ISSUE_A(buf_, kt_, o);                               \
     } while (0)
     // staging instruction of B for slot m_ (0 .. NM-1, substep 3): every (NM/NIB)-th slot
 #define ISSUE_B_AT(m_, buf_, kt_)                                                                \
     do {                                                                                         \
         _Pragma("unroll") for (int o = 0; o < NIB; ++o)                                          \
-            if (o * (NM / NIB) == (m_)) ISSUE_B(buf_, kt_, o);                                   \
+            if (o * BSTR == (m_)) ISSUE_B(buf_, kt_, o);                                   \
     } while (0)
     // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
     // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
@@ -743,6 +766,18 @@ int wgrad_chunk_len(const MoeDims& D) {
     return (int)L;
 }
 
+// Capacities of the work lists (see build_worklists): row tiles, token-contraction items.
+static int worklist_rt_cap(const MoeDims& D) { return D.A / TBM + D.E; }
+static int worklist_it_cap(const MoeDims& D) { return D.A / wgrad_chunk_len(D) + D.E; }
+size_t gemm_worklist_ints(const MoeDims& D) {
+    return 4 + 4 * (size_t)worklist_rt_cap(D) + 4 * (size_t)worklist_it_cap(D);
+}
+static void launch_worklists(const MoeDims& D, const hexa_moe_idx& idx, const MoeWorkspace& ws, hipStream_t st) {
+    ProfScope ps(st, "worklists");
+    hipLaunchKernelGGL(build_worklists, dim3(1), dim3(1024), 0, st, idx.offsets, D.E, TBM,
+                       wgrad_chunk_len(D), ws.worklist, worklist_rt_cap(D));
+}
+
 // Upper bound on split-K slots: only experts with more than one chunk use slots, and
 // sum over those of ceil(n_e / L) <= 2 A / L.
 size_t wgrad_max_slots(const MoeDims& D) {
@@ -754,6 +789,8 @@ hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
                            const MoeWorkspace& ws, hipStream_t st) {
     GemmArgs g{};
     g.offsets = idx.offsets; g.perm = idx.perm; g.topk = D.k; g.E = D.E;
+    g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
+    launch_worklists(D, idx, ws, st);
     g.A = x; g.a_rows = D.T; g.B = W1; g.bias = b1; g.out0 = ws.pre; g.out1 = ws.h; g.K = D.d; g.N = D.f;
     launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st, "fc1");
     g.A = (const bf16_t*)ws.h; g.B = W2; g.bias = b2; g.out0 = ws.o; g.out1 = nullptr; g.K = D.f; g.N = D.d;
@@ -767,6 +804,8 @@ hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     GemmArgs g{};
     g.offsets = idx.offsets; g.perm = idx.perm; g.topk = D.k; g.E = D.E;
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
+    g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
+    launch_worklists(D, idx, ws, st);
     // dpre = (do W2^T) * GELU'(pre)
     g.A = (const bf16_t*)ws.dout; g.B = W2; g.pre_in = (const bf16_t*)ws.pre; g.out0 = ws.dpre;
     g.colpart = ws.colpart;
