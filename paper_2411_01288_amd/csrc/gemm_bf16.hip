@@ -547,6 +547,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     // leave as full 256- or 512-byte row segments.  DGRAD2's saved pre-activations come in the
     // same way, staged one band ahead.
     __syncthreads();   // every wave is done reading fragments
+#define STORE16(p_, v_) (*reinterpret_cast<u32x4*>(p_) = (v_))
     {
         uint8_t* wreg = smem + uwave * 32768;
         constexpr bool OUT_F32 = TOKENS || OP == OP_FC2 || OP == OP_DGRAD1;
@@ -645,24 +646,21 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                 const int c = (lane % CPRO) ^ (row & (CPRO - 1));
                 const int col = wcol0 + c * (16 / ESZ);
                 const int trow = wrow0 + i * 32 + row;
-#ifdef HEXA_DBG_NOEPI
-                if (acc[i][0][t % 16] != 12345.f) continue;
-#endif
                 const bool ok = trow < mvalid && col < nvalid;
                 const size_t oi = (size_t)(m0 + trow) * ldo + (size_t)(n0 + col);
                 const u32x4 d0 = *reinterpret_cast<const u32x4*>(wreg + t * 1024 + lane * 16);
                 if constexpr (OP == OP_FC1) {
                     const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + 8192 + t * 1024 + lane * 16);
                     if (ok) {
-                        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d0;
-                        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out1) + oi) = d1;
+                        STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
+                        STORE16(reinterpret_cast<bf16_t*>(g.out1) + oi, d1);
                     }
                 } else if constexpr (OP == OP_DGRAD2) {
-                    if (ok) *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(g.out0) + oi) = d0;
+                    if (ok) STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
                 } else if constexpr (TOKENS) {
-                    if (ok) *reinterpret_cast<u32x4*>(tok_out + oi) = d0;
+                    if (ok) STORE16(tok_out + oi, d0);
                 } else {
-                    if (ok) *reinterpret_cast<u32x4*>(reinterpret_cast<float*>(g.out0) + oi) = d0;
+                    if (ok) STORE16(reinterpret_cast<float*>(g.out0) + oi, d0);
                 }
             }
         }
@@ -673,6 +671,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                     make_float2(cs0, cs1);
         }
     }
+#undef STORE16
 }
 
 // Second stage of the split token contraction, plus exact zeros for experts without tokens.
