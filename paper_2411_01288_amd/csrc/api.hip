@@ -61,10 +61,10 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
     };
     w.pre = take(A * f * es);
     w.h = take(A * f * es);
-    w.o = (float*)take(A * d * 4);
+    w.o = take(A * d * es);
     w.dout = take(A * d * es);
     w.dpre = take(A * f * es);
-    w.dxp = (float*)take(A * d * 4);
+    w.dxp = take(A * d * es);
     w.colpart = (float*)take((A / 128 + 2 * (size_t)D.E) * (d > f ? d : f) * 4);
     if (dtype == HEXA_BF16) {
         w.xg = take(A * d * es);
@@ -168,11 +168,11 @@ hexa_status hexa_moe_fwd(const hexa_moe_shape* shape, const void* x, const int32
     if (shape->dtype == HEXA_F32) {
         e = launch_f32_fwd(D, (const float*)x, (const float*)W1, (const float*)b1, (const float*)W2,
                            (const float*)b2, idx, ws, st);
-        if (e == hipSuccess) e = launch_combine_y<float>(D, ws.o, idx.inv, gate, (float*)y, st);
+        if (e == hipSuccess) e = launch_combine_y<float>(D, (const float*)ws.o, idx.inv, gate, (float*)y, st);
     } else {
         e = launch_bf16_fwd(D, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)b1,
                             (const bf16_t*)W2, (const bf16_t*)b2, idx, ws, st);
-        if (e == hipSuccess) e = launch_combine_y<bf16_t>(D, ws.o, idx.inv, gate, (bf16_t*)y, st);
+        if (e == hipSuccess) e = launch_combine_y<bf16_t>(D, (const bf16_t*)ws.o, idx.inv, gate, (bf16_t*)y, st);
     }
     return dev(e);
 }
@@ -192,7 +192,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
     if (shape->dtype == HEXA_F32) {
-        e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, ws.o, idx.perm,
+        e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, (const float*)ws.o, idx.perm,
                                        idx.offsets, gate, (float*)ws.dout, dgate, st);
         if (e == hipSuccess)
             e = launch_segment_colsum<float>(D, (const float*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
@@ -200,9 +200,9 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
             e = launch_f32_bwd(D, (const float*)x, (const float*)W1, (const float*)W2, idx, ws, dW1, dW2, st);
         if (e == hipSuccess)
             e = launch_segment_colsum<float>(D, (const float*)ws.dpre, D.f, idx.offsets, ws.colpart, db1, st);
-        if (e == hipSuccess) e = launch_combine_dx<float>(D, ws.dxp, idx.inv, (float*)dx, st);
+        if (e == hipSuccess) e = launch_combine_dx<float>(D, (const float*)ws.dxp, idx.inv, (float*)dx, st);
     } else {
-        e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, ws.o,
+        e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, (const bf16_t*)ws.o,
                                         idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, st);
         if (e == hipSuccess)
             e = launch_segment_colsum<bf16_t>(D, (const bf16_t*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
@@ -211,7 +211,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
                                 dW1, dW2, st);
         if (e == hipSuccess)
             e = launch_tile_colsum_finish(D, ws.colpart, D.f, idx.offsets, db1, st);
-        if (e == hipSuccess) e = launch_combine_dx<bf16_t>(D, ws.dxp, idx.inv, (bf16_t*)dx, st);
+        if (e == hipSuccess) e = launch_combine_dx<bf16_t>(D, (const bf16_t*)ws.dxp, idx.inv, (bf16_t*)dx, st);
     }
     return dev(e);
 }

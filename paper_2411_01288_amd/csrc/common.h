@@ -83,10 +83,10 @@ struct MoeDims { int T, d, f, E, k, A; };
 struct MoeWorkspace {
     void* pre;      // [A,f] elem   pre-activations, perm order        (saved by fwd)
     void* h;        // [A,f] elem   activations, perm order            (saved by fwd)
-    float* o;       // [A,d] f32    per-assignment expert outputs      (saved by fwd)
+    void* o;        // [A,d] elem   per-assignment expert outputs      (saved by fwd)
     void* dout;     // [A,d] elem   gate * dY gathered to perm order   (bwd staging)
     void* dpre;     // [A,f] elem                                       (bwd staging)
-    float* dxp;     // [A,d] f32    per-assignment input gradients     (bwd staging)
+    void* dxp;      // [A,d] elem   per-assignment input gradients     (bwd staging)
     void* xg;       // [A,d] elem   x gathered to perm order (bf16 path)(bwd staging)
     float* colpart; // [A/128+2E, max(d,f)] f32 partial column sums    (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
@@ -106,15 +106,15 @@ hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx 
 size_t index_scratch_bytes(const MoeDims& D);
 
 template <typename T>
-hipError_t launch_combine_y(const MoeDims& D, const float* o, const int32_t* inv, const float* gate,
+hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,
                             T* y, hipStream_t st);
 // dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, and (when xg != NULL) xg_p = x_t, for a = perm[p]
 template <typename T>
-hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const float* o,
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
                                T* dout, float* dgate, hipStream_t st);
 template <typename T>
-hipError_t launch_combine_dx(const MoeDims& D, const float* dxp, const int32_t* inv, T* dx,
+hipError_t launch_combine_dx(const MoeDims& D, const T* dxp, const int32_t* inv, T* dx,
                              hipStream_t st);
 // ESS: out[e][c] = sum over the expert's rows of src[p][c]; src is [A, ncols] in perm order
 template <typename T>

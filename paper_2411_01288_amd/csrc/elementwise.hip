@@ -43,7 +43,7 @@ template <> struct Vec<bf16_t> {
 // One thread per VN consecutive columns of one token.  d % VN == 0.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_rows(int T_, int d, int k,
-                                                    const float* __restrict__ src,
+                                                    const T* __restrict__ src,
                                                     const int32_t* __restrict__ inv,
                                                     const float* __restrict__ gate,  // NULL: plain sum
                                                     T* __restrict__ dst) {
@@ -60,12 +60,10 @@ __global__ __launch_bounds__(256) void combine_rows(int T_, int d, int k,
         const int p = inv[(size_t)t * k + j];
         if (p < 0) continue;  // dropped assignment
         const float g = gate ? gate[(size_t)t * k + j] : 1.f;
-        const float* s = src + (size_t)p * d + c;
+        float v[VN];
+        Vec<T>::load(src + (size_t)p * d + c, v);
 #pragma unroll
-        for (int q = 0; q < VN; q += 4) {
-            const float4 v = *reinterpret_cast<const float4*>(s + q);
-            acc[q] += g * v.x; acc[q + 1] += g * v.y; acc[q + 2] += g * v.z; acc[q + 3] += g * v.w;
-        }
+        for (int q = 0; q < VN; ++q) acc[q] += g * v[q];
     }
     Vec<T>::store(dst + (size_t)t * d + c, acc);
 }
@@ -73,7 +71,7 @@ __global__ __launch_bounds__(256) void combine_rows(int T_, int d, int k,
 // Tail columns when d is not a multiple of the vector width (fp32 path with odd sizes).
 template <typename T>
 __global__ __launch_bounds__(256) void combine_rows_scalar(int T_, int d, int k,
-                                                           const float* __restrict__ src,
+                                                           const T* __restrict__ src,
                                                            const int32_t* __restrict__ inv,
                                                            const float* __restrict__ gate,
                                                            T* __restrict__ dst) {
@@ -85,7 +83,7 @@ __global__ __launch_bounds__(256) void combine_rows_scalar(int T_, int d, int k,
         const int p = inv[(size_t)t * k + j];
         if (p < 0) continue;
         const float g = gate ? gate[(size_t)t * k + j] : 1.f;
-        acc += g * src[(size_t)p * d + c];
+        acc += g * Elem<T>::ld(src + (size_t)p * d + c);
     }
     Elem<T>::st(dst + (size_t)t * d + c, acc);
 }
@@ -94,7 +92,7 @@ __global__ __launch_bounds__(256) void combine_rows_scalar(int T_, int d, int k,
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T* __restrict__ dY,
                                                     const T* __restrict__ x, T* __restrict__ xg,
-                                                    const float* __restrict__ o,
+                                                    const T* __restrict__ o,
                                                     const int32_t* __restrict__ perm,
                                                     const int32_t* __restrict__ offsets, int E,
                                                     const float* __restrict__ gate,
@@ -114,19 +112,17 @@ __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T
     const int t = a / k;
     const float g = gate[a];
     const T* src = dY + (size_t)t * d;
-    const float* orow = o + (size_t)p * d;
+    const T* orow = o + (size_t)p * d;
     T* dst = dout + (size_t)p * d;
     float dot = 0.f;
     constexpr int VN = Vec<T>::N;
     if (d % VN == 0) {
         for (int c = lane * VN; c < d; c += 64 * VN) {
-            float v[VN], w[VN];
+            float v[VN], w[VN], ov[VN];
             Vec<T>::load(src + c, v);
+            Vec<T>::load(orow + c, ov);
 #pragma unroll
-            for (int q = 0; q < VN; q += 4) {
-                const float4 ov = *reinterpret_cast<const float4*>(orow + c + q);
-                dot += v[q] * ov.x + v[q + 1] * ov.y + v[q + 2] * ov.z + v[q + 3] * ov.w;
-            }
+            for (int q = 0; q < VN; ++q) dot += v[q] * ov[q];
 #pragma unroll
             for (int q = 0; q < VN; ++q) w[q] = g * v[q];
             Vec<T>::store(dst + c, w);
@@ -137,7 +133,7 @@ __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T
     } else {
         for (int c = lane; c < d; c += 64) {
             const float v = Elem<T>::ld(src + c);
-            dot += v * orow[c];
+            dot += v * Elem<T>::ld(orow + c);
             Elem<T>::st(dst + c, g * v);
             if (xg) xg[(size_t)p * d + c] = x[(size_t)t * d + c];
         }
@@ -205,7 +201,7 @@ __global__ __launch_bounds__(256) void tile_colsum_finish(const float* __restric
 }
 
 template <typename T>
-hipError_t combine_impl(int T_, int d, int k, const float* src, const int32_t* inv,
+hipError_t combine_impl(int T_, int d, int k, const T* src, const int32_t* inv,
                         const float* gate, T* dst, hipStream_t st) {
     ProfScope ps(st, gate ? "combine_y" : "combine_dx");
     constexpr int VN = Vec<T>::N;
@@ -224,19 +220,19 @@ hipError_t combine_impl(int T_, int d, int k, const float* src, const int32_t* i
 }  // namespace
 
 template <typename T>
-hipError_t launch_combine_y(const MoeDims& D, const float* o, const int32_t* inv, const float* gate,
+hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,
                             T* y, hipStream_t st) {
     return combine_impl<T>(D.T, D.d, D.k, o, inv, gate, y, st);
 }
 
 template <typename T>
-hipError_t launch_combine_dx(const MoeDims& D, const float* dxp, const int32_t* inv, T* dx,
+hipError_t launch_combine_dx(const MoeDims& D, const T* dxp, const int32_t* inv, T* dx,
                              hipStream_t st) {
     return combine_impl<T>(D.T, D.d, D.k, dxp, inv, nullptr, dx, st);
 }
 
 template <typename T>
-hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const float* o,
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
                                T* dout, float* dgate, hipStream_t st) {
     ProfScope ps(st, "bwd_prologue");
@@ -271,12 +267,12 @@ hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int
 }
 
 #define INSTANTIATE(T)                                                                              \
-    template hipError_t launch_combine_y<T>(const MoeDims&, const float*, const int32_t*,          \
+    template hipError_t launch_combine_y<T>(const MoeDims&, const T*, const int32_t*,              \
                                             const float*, T*, hipStream_t);                        \
-    template hipError_t launch_combine_dx<T>(const MoeDims&, const float*, const int32_t*, T*,     \
+    template hipError_t launch_combine_dx<T>(const MoeDims&, const T*, const int32_t*, T*,         \
                                              hipStream_t);                                         \
     template hipError_t launch_bwd_prologue<T>(const MoeDims&, const T*, const T*, T*,             \
-                                               const float*, const int32_t*, const int32_t*,       \
+                                               const T*, const int32_t*, const int32_t*,           \
                                                const float*, T*, float*, hipStream_t);             \
     template hipError_t launch_segment_colsum<T>(const MoeDims&, const T*, int, const int32_t*,    \
                                                  float*, float*, hipStream_t);

@@ -133,7 +133,7 @@ hipError_t launch_f32_fwd(const MoeDims& D, const float* x, const float* W1, con
     // fc2: o = h W2 + b2
     a.A = (const float*)ws.h; a.lda = D.f; a.gather = 0;
     a.B = W2; a.b_expert_stride = (size_t)D.f * D.d; a.sbk = D.d; a.sbn = 1;
-    a.bias = b2; a.out0 = ws.o; a.out1 = nullptr; a.K = D.f; a.N = D.d; a.mode = F32_FC2;
+    a.bias = b2; a.out0 = (float*)ws.o; a.out1 = nullptr; a.K = D.f; a.N = D.d; a.mode = F32_FC2;
     rows_launch(D, a, st);
     return hipGetLastError();
 }
@@ -151,7 +151,7 @@ hipError_t launch_f32_bwd(const MoeDims& D, const float* x, const float* W1, con
     // dxp = dpre W1^T
     a.A = (const float*)ws.dpre; a.lda = D.f;
     a.B = W1; a.b_expert_stride = (size_t)D.d * D.f; a.sbk = 1; a.sbn = D.f;
-    a.pre_in = nullptr; a.out0 = ws.dxp; a.K = D.f; a.N = D.d; a.mode = F32_DGRAD1;
+    a.pre_in = nullptr; a.out0 = (float*)ws.dxp; a.K = D.f; a.N = D.d; a.mode = F32_DGRAD1;
     rows_launch(D, a, st);
     // dW2[e] = h^T do ; dW1[e] = x^T dpre
     WgradArgs w{};

@@ -3,9 +3,9 @@
 // Six contractions share one kernel template:
 //   row GEMMs  (ESMM, App. B Alg. 2): rows are one expert segment of the re-index vector
 //       FC1     pre = x[perm/k] W1[e] + b1[e],  h = GELU(pre)        K = d, N = f
-//       FC2     o   = h W2[e] + b2[e]                                K = f, N = d
+//       FC2     o   = h W2[e] + b2[e]   (stored as bf16)                 K = f, N = d
 //       DGRAD2  dpre = (do W2[e]^T) * GELU'(pre)                     K = d, N = f
-//       DGRAD1  dxp = dpre W1[e]^T                                   K = f, N = d
+//       DGRAD1  dxp = dpre W1[e]^T      (stored as bf16)                 K = f, N = d
 //   token contractions (ESTMM, App. B Alg. 4): the sum runs over one expert's rows
 //       WGRAD2  dW2[e] = h^T do                                      M = f, N = d
 //       WGRAD1  dW1[e] = xg^T dpre                                   M = d, N = f
@@ -550,7 +550,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #define STORE16(p_, v_) (*reinterpret_cast<u32x4*>(p_) = (v_))
     {
         uint8_t* wreg = smem + uwave * 32768;
-        constexpr bool OUT_F32 = TOKENS || OP == OP_FC2 || OP == OP_DGRAD1;
+        constexpr bool OUT_F32 = TOKENS;   // weight gradients; every activation-like output is bf16
         constexpr int ESZ = OUT_F32 ? 4 : 2;
         constexpr int RPB = TN * ESZ;                 // bytes per staged row (TN columns)
         constexpr int CPRO = RPB / 16;                // 16-byte chunks per staged row
@@ -615,6 +615,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                             hz.y = pack_bf2(gelu_fast(v[2]), gelu_fast(v[3]));
                             *reinterpret_cast<u32x2*>(wreg + off) = pz;
                             *reinterpret_cast<u32x2*>(wreg + 8192 + off) = hz;
+                        } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
+                            u32x2 z;
+                            z.x = pack_bf2(v[0], v[1]); z.y = pack_bf2(v[2], v[3]);
+                            *reinterpret_cast<u32x2*>(wreg + off) = z;
                         } else {   // DGRAD2
                             const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + 16384 + (i & 1) * 8192 + off);
                             const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
@@ -655,12 +659,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
                         STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
                         STORE16(reinterpret_cast<bf16_t*>(g.out1) + oi, d1);
                     }
-                } else if constexpr (OP == OP_DGRAD2) {
-                    if (ok) STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
                 } else if constexpr (TOKENS) {
                     if (ok) STORE16(tok_out + oi, d0);
                 } else {
-                    if (ok) STORE16(reinterpret_cast<float*>(g.out0) + oi, d0);
+                    if (ok) STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
                 }
             }
         }
