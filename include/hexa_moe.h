@@ -105,8 +105,9 @@ HEXA_API hexa_status hexa_moe_index(const hexa_moe_shape *shape, const int32_t *
  *   y [T,d]    dev, out, shape.dtype
  *   workspace  dev, >= hexa_moe_workspace_bytes(); afterwards holds the saved
  *              state hexa_moe_bwd reads
- * bf16: products in bf16 MFMA with fp32 accumulation; pre, h are stored
- * rounded to bf16 (round-to-nearest-even). */
+ * bf16: products in bf16 MFMA with fp32 accumulation; pre, h and the per-assignment
+ * outputs o are stored rounded to bf16 (round-to-nearest-even), the k-slot sum runs
+ * in fp32. */
 HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, const int32_t *topk_idx,
                          const float *gate, const void *W1, const void *b1, const void *W2,
                          const void *b2, hexa_moe_idx idx, void *y, void *workspace,

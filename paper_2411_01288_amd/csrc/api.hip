@@ -193,9 +193,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
     hipError_t e;
     if (shape->dtype == HEXA_F32) {
         e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, (const float*)ws.o, idx.perm,
-                                       idx.offsets, gate, (float*)ws.dout, dgate, st);
-        if (e == hipSuccess)
-            e = launch_segment_colsum<float>(D, (const float*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
+                                       idx.offsets, gate, (float*)ws.dout, dgate, ws.colpart, db2, st);
         if (e == hipSuccess)
             e = launch_f32_bwd(D, (const float*)x, (const float*)W1, (const float*)W2, idx, ws, dW1, dW2, st);
         if (e == hipSuccess)
@@ -203,9 +201,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
         if (e == hipSuccess) e = launch_combine_dx<float>(D, (const float*)ws.dxp, idx.inv, (float*)dx, st);
     } else {
         e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, (const bf16_t*)ws.o,
-                                        idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, st);
-        if (e == hipSuccess)
-            e = launch_segment_colsum<bf16_t>(D, (const bf16_t*)ws.dout, D.d, idx.offsets, ws.colpart, db2, st);
+                                        idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, ws.colpart, db2, st);
         if (e == hipSuccess)
             e = launch_bf16_bwd(D, (const bf16_t*)ws.xg, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
                                 dW1, dW2, st);

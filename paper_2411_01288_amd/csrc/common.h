@@ -108,11 +108,12 @@ size_t index_scratch_bytes(const MoeDims& D);
 template <typename T>
 hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,
                             T* y, hipStream_t st);
-// dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, and (when xg != NULL) xg_p = x_t, for a = perm[p]
+// dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, (when xg != NULL) xg_p = x_t, for a = perm[p], and
+// db2[e] = sum over the expert's rows of gate_a dY_t (ESS; `partial` is column-sum staging)
 template <typename T>
 hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
-                               T* dout, float* dgate, hipStream_t st);
+                               T* dout, float* dgate, float* partial, float* db2, hipStream_t st);
 template <typename T>
 hipError_t launch_combine_dx(const MoeDims& D, const T* dxp, const int32_t* inv, T* dx,
                              hipStream_t st);

@@ -2,7 +2,7 @@
 //   combine_y      y_t  = sum_j gate[t,j] * o[inv[t*k+j]]          (top-k sum of App. B Table 5 row 3,
 //                                                                    done as a gather in fixed slot order
 //                                                                    instead of the paper's atomicAdd)
-//   bwd_prologue   do_p = gate_a * dY_t  (a = perm[p]) ; dgate_a = <dY_t, o_p>
+//   bwd_prologue   do_p = gate_a * dY_t  (a = perm[p]) ; dgate_a = <dY_t, o_p> ; db2 partials
 //   combine_dx     dx_t = sum_j dxp[inv[t*k+j]]                     (Table 5 row 10, sum over the k slots)
 //   segment_colsum ESS (Sec. 3.1 item 2; App. B Alg. 3): per-expert column sums of a perm-ordered
 //                  matrix, in two deterministic stages so a long segment is spread over the chip.
@@ -183,6 +183,86 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ p
     out[(size_t)e * ncols + c] = acc;
 }
 
+// Backward prologue and the fc2 bias gradient in one pass (ESS, Sec. 3.1 item 2; Table 5 row 4):
+// one workgroup per 128-row segment tile; a thread owns VN consecutive columns (256*VN columns per
+// sweep) and walks the tile's rows in order, so the column sums of do = gate * dY (unrounded) stay
+// in registers and go to partial[tile][col] for colsum_stage2.  Per row it also writes
+// dout_p = round(do), xg_p = x_t and accumulates <dY_t, o_p> (wave sums meet in LDS, added in wave
+// order).  Workgroups past the last tile zero the rows past the last segment (they exist only
+// when expert ids were dropped).  d % VN == 0.
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, const T* __restrict__ dY,
+                                                          const T* __restrict__ x, T* __restrict__ xg,
+                                                          const T* __restrict__ o,
+                                                          const int32_t* __restrict__ perm,
+                                                          const int32_t* __restrict__ offsets, int E,
+                                                          const float* __restrict__ gate,
+                                                          T* __restrict__ dout, float* __restrict__ dgate,
+                                                          float* __restrict__ partial) {
+    constexpr int VN = Vec<T>::N;
+    __shared__ float sdot[kColsumRows][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const SegTile s = seg_tile_find(offsets, E, kColsumRows, blockIdx.x);
+    if (s.e < 0) {
+        const int ntiles = seg_tiles_total(offsets, E, kColsumRows);
+        const long long r0 = (long long)offsets[E] + (long long)(blockIdx.x - ntiles) * kColsumRows;
+        float z[VN];
+#pragma unroll
+        for (int q = 0; q < VN; ++q) z[q] = 0.f;
+        for (long long r = r0; r < r0 + kColsumRows && r < A; ++r)
+            for (int c = tid * VN; c < d; c += 256 * VN) {
+                Vec<T>::store(dout + (size_t)r * d + c, z);
+                if (xg) Vec<T>::store(xg + (size_t)r * d + c, z);
+            }
+        return;
+    }
+    for (int c0 = 0; c0 < d; c0 += 256 * VN) {
+        const int c = c0 + tid * VN;
+        const bool act = c < d;
+        float cs[VN];
+#pragma unroll
+        for (int q = 0; q < VN; ++q) cs[q] = 0.f;
+        for (int r = 0; r < s.rows; ++r) {
+            const int p = s.row0 + r;
+            const int a = perm[p];
+            const int t = a / k;
+            const float g = gate[a];
+            float dot = 0.f;
+            if (act) {
+                float v[VN], ov[VN], w[VN];
+                Vec<T>::load(dY + (size_t)t * d + c, v);
+                Vec<T>::load(o + (size_t)p * d + c, ov);
+#pragma unroll
+                for (int q = 0; q < VN; ++q) {
+                    dot += v[q] * ov[q];
+                    w[q] = g * v[q];
+                    cs[q] += w[q];
+                }
+                Vec<T>::store(dout + (size_t)p * d + c, w);
+                if (xg)
+                    *reinterpret_cast<uint4*>(xg + (size_t)p * d + c) =
+                        *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
+            }
+            if (dgate) {
+#pragma unroll
+                for (int sh = 32; sh > 0; sh >>= 1) dot += __shfl_xor(dot, sh);
+                if (lane == 0) sdot[r][wave] = (c0 == 0 ? 0.f : sdot[r][wave]) + dot;
+            }
+        }
+        if (act) {
+            float* dst = partial + (size_t)blockIdx.x * d + c;
+#pragma unroll
+            for (int q = 0; q < VN; q += 4)
+                *reinterpret_cast<float4*>(dst + q) = make_float4(cs[q], cs[q + 1], cs[q + 2], cs[q + 3]);
+        }
+    }
+    if (dgate) {
+        __syncthreads();
+        if (tid < s.rows)
+            dgate[perm[s.row0 + tid]] = ((sdot[tid][0] + sdot[tid][1]) + sdot[tid][2]) + sdot[tid][3];
+    }
+}
+
 // out[e][c] = sum over the expert's row tiles (tile height bm, `parts` partial rows per tile) of
 // partial[tile*parts + q][c], in order; exact 0 for an expert without rows.
 __global__ __launch_bounds__(256) void tile_colsum_finish(const float* __restrict__ partial, int ncols,
@@ -234,15 +314,29 @@ hipError_t launch_combine_dx(const MoeDims& D, const T* dxp, const int32_t* inv,
 template <typename T>
 hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
-                               T* dout, float* dgate, hipStream_t st) {
-    ProfScope ps(st, "bwd_prologue");
+                               T* dout, float* dgate, float* partial, float* db2, hipStream_t st) {
     if (dgate) {  // dropped assignments keep a defined (zero) gate gradient
+        ProfScope ps(st, "dgate_zero");
         const size_t n = (size_t)D.A;
         hipLaunchKernelGGL(fill_zero_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dgate, n);
     }
-    hipLaunchKernelGGL(bwd_prologue<T>, dim3(ceil_div(D.A, 4)), dim3(256), 0, st, D.A, D.d, D.k, dY,
-                       x, xg, o, perm, offsets, D.E, gate, dout, dgate);
-    return hipGetLastError();
+    if (D.d % Vec<T>::N == 0) {
+        {
+            ProfScope ps(st, "bwd_prologue");
+            hipLaunchKernelGGL(bwd_prologue_tiles<T>, dim3(D.A / kColsumRows + D.E + 1), dim3(256), 0, st,
+                               D.A, D.d, D.k, dY, x, xg, o, perm, offsets, D.E, gate, dout, dgate, partial);
+        }
+        ProfScope ps(st, "colsum_db2");
+        hipLaunchKernelGGL(colsum_stage2, dim3(D.E, ceil_div(D.d, 256)), dim3(256), 0, st, partial, D.d,
+                           D.E, offsets, db2);
+        return hipGetLastError();
+    }
+    {
+        ProfScope ps(st, "bwd_prologue");
+        hipLaunchKernelGGL(bwd_prologue<T>, dim3(ceil_div(D.A, 4)), dim3(256), 0, st, D.A, D.d, D.k, dY,
+                           x, xg, o, perm, offsets, D.E, gate, dout, dgate);
+    }
+    return launch_segment_colsum<T>(D, dout, D.d, offsets, partial, db2, st);
 }
 
 template <typename T>
@@ -273,7 +367,8 @@ hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int
                                              hipStream_t);                                         \
     template hipError_t launch_bwd_prologue<T>(const MoeDims&, const T*, const T*, T*,             \
                                                const T*, const int32_t*, const int32_t*,           \
-                                               const float*, T*, float*, hipStream_t);             \
+                                               const float*, T*, float*, float*, float*,           \
+                                               hipStream_t);                                       \
     template hipError_t launch_segment_colsum<T>(const MoeDims&, const T*, int, const int32_t*,    \
                                                  float*, float*, hipStream_t);
 INSTANTIATE(float)
