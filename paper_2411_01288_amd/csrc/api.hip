@@ -65,7 +65,12 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
     w.dout = take(A * d * es);
     w.dpre = take(A * f * es);
     w.dxp = take(A * d * es);
-    w.colpart = (float*)take((A / 128 + 2 * (size_t)D.E) * (d > f ? d : f) * 4);
+    {   // column-sum staging: the prologue's tiles, or (bf16) two partial rows per 256-row GEMM tile
+        size_t rows = colsum_partial_rows(D);
+        const size_t rows_gemm = A / 128 + 2 * (size_t)D.E;
+        if (rows < rows_gemm) rows = rows_gemm;
+        w.colpart = (float*)take(rows * (d > f ? d : f) * 4);
+    }
     if (dtype == HEXA_BF16) {
         w.xg = take(A * d * es);
         w.kpart_slots = wgrad_max_slots(D);

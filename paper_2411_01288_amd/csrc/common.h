@@ -88,7 +88,7 @@ struct MoeWorkspace {
     void* dpre;     // [A,f] elem                                       (bwd staging)
     void* dxp;      // [A,d] elem   per-assignment input gradients     (bwd staging)
     void* xg;       // [A,d] elem   x gathered to perm order (bf16 path)(bwd staging)
-    float* colpart; // [A/128+2E, max(d,f)] f32 partial column sums    (bwd staging)
+    float* colpart; // [rows, max(d,f)] f32 partial column sums          (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
     size_t kpart_slots;
     int32_t* worklist; // row tiles and token-contraction items of the bf16 kernels (rebuilt by fwd and bwd)
@@ -99,7 +99,9 @@ int gemm_row_tile();                 // rows of a bf16 row-GEMM tile
 int gemm_colpart_rows_per_tile();    // DGRAD2 writes this many column-sum partial rows per row tile
 int wgrad_chunk_len(const MoeDims& D);          // tokens per split-K chunk (host policy)
 size_t wgrad_max_slots(const MoeDims& D);
-size_t gemm_worklist_ints(const MoeDims& D);    // int32 entries of MoeWorkspace::worklist
+size_t gemm_worklist_ints(const MoeDims& D);
+int bwd_prologue_tile_rows(const MoeDims& D);   // rows per workgroup of the fused backward prologue
+size_t colsum_partial_rows(const MoeDims& D);   // rows of MoeWorkspace::colpart the column sums need    // int32 entries of MoeWorkspace::worklist
 
 hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx out, void* scratch,
                         hipStream_t st);

@@ -170,21 +170,23 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ src, 
 
 // Stage 2: out[e][c] = sum of the expert's tile partials in tile order (exact 0 for an empty expert).
 __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int ncols,
-                                                     int E, const int32_t* __restrict__ offsets,
+                                                     int E, int tile_rows,
+                                                     const int32_t* __restrict__ offsets,
                                                      float* __restrict__ out) {
     const int e = blockIdx.x;
     const int c = blockIdx.y * 256 + threadIdx.x;
     if (c >= ncols) return;
     int first = 0;
-    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], kColsumRows);
-    const int nt = ceil_div(offsets[e + 1] - offsets[e], kColsumRows);
+    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], tile_rows);
+    const int nt = ceil_div(offsets[e + 1] - offsets[e], tile_rows);
     float acc = 0.f;
+#pragma unroll 8
     for (int i = 0; i < nt; ++i) acc += partial[(size_t)(first + i) * ncols + c];
     out[(size_t)e * ncols + c] = acc;
 }
 
 // Backward prologue and the fc2 bias gradient in one pass (ESS, Sec. 3.1 item 2; Table 5 row 4):
-// one workgroup per 128-row segment tile; a thread owns VN consecutive columns (256*VN columns per
+// one workgroup per segment tile of tile_rows <= 128 rows; a thread owns VN consecutive columns (256*VN columns per
 // sweep) and walks the tile's rows in order, so the column sums of do = gate * dY (unrounded) stay
 // in registers and go to partial[tile][col] for colsum_stage2.  Per row it also writes
 // dout_p = round(do), xg_p = x_t and accumulates <dY_t, o_p> (wave sums meet in LDS, added in wave
@@ -198,18 +200,18 @@ __global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, c
                                                           const int32_t* __restrict__ offsets, int E,
                                                           const float* __restrict__ gate,
                                                           T* __restrict__ dout, float* __restrict__ dgate,
-                                                          float* __restrict__ partial) {
+                                                          float* __restrict__ partial, int tile_rows) {
     constexpr int VN = Vec<T>::N;
     __shared__ float sdot[kColsumRows][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const SegTile s = seg_tile_find(offsets, E, kColsumRows, blockIdx.x);
+    const SegTile s = seg_tile_find(offsets, E, tile_rows, blockIdx.x);
     if (s.e < 0) {
-        const int ntiles = seg_tiles_total(offsets, E, kColsumRows);
-        const long long r0 = (long long)offsets[E] + (long long)(blockIdx.x - ntiles) * kColsumRows;
+        const int ntiles = seg_tiles_total(offsets, E, tile_rows);
+        const long long r0 = (long long)offsets[E] + (long long)(blockIdx.x - ntiles) * tile_rows;
         float z[VN];
 #pragma unroll
         for (int q = 0; q < VN; ++q) z[q] = 0.f;
-        for (long long r = r0; r < r0 + kColsumRows && r < A; ++r)
+        for (long long r = r0; r < r0 + tile_rows && r < A; ++r)
             for (int c = tid * VN; c < d; c += 256 * VN) {
                 Vec<T>::store(dout + (size_t)r * d + c, z);
                 if (xg) Vec<T>::store(xg + (size_t)r * d + c, z);
@@ -276,6 +278,7 @@ __global__ __launch_bounds__(256) void tile_colsum_finish(const float* __restric
     for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], bm);
     const int nt = ceil_div(offsets[e + 1] - offsets[e], bm);
     float acc = 0.f;
+#pragma unroll 8
     for (int i = 0; i < nt * parts; ++i) acc += partial[(size_t)(first * parts + i) * ncols + c];
     out[(size_t)e * ncols + c] = acc;
 }
@@ -299,6 +302,19 @@ hipError_t combine_impl(int T_, int d, int k, const T* src, const int32_t* inv,
 
 }  // namespace
 
+// Rows per workgroup of the fused backward prologue: 128 when that still gives ~2048 workgroups,
+// fewer (down to 8) on small problems, where a workgroup's serial walk over its rows would
+// otherwise be the whole run time.
+int bwd_prologue_tile_rows(const MoeDims& D) {
+    int r = kColsumRows;
+    while (r > 8 && D.A / r < 2048) r >>= 1;
+    return r;
+}
+// Rows of the column-sum staging buffer that the prologue and the two-stage column sums need.
+size_t colsum_partial_rows(const MoeDims& D) {
+    return (size_t)(D.A / bwd_prologue_tile_rows(D) + D.E + 1);
+}
+
 template <typename T>
 hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,
                             T* y, hipStream_t st) {
@@ -321,14 +337,15 @@ hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg,
         hipLaunchKernelGGL(fill_zero_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dgate, n);
     }
     if (D.d % Vec<T>::N == 0) {
+        const int R = bwd_prologue_tile_rows(D);
         {
             ProfScope ps(st, "bwd_prologue");
-            hipLaunchKernelGGL(bwd_prologue_tiles<T>, dim3(D.A / kColsumRows + D.E + 1), dim3(256), 0, st,
-                               D.A, D.d, D.k, dY, x, xg, o, perm, offsets, D.E, gate, dout, dgate, partial);
+            hipLaunchKernelGGL(bwd_prologue_tiles<T>, dim3(D.A / R + D.E + 1), dim3(256), 0, st, D.A, D.d,
+                               D.k, dY, x, xg, o, perm, offsets, D.E, gate, dout, dgate, partial, R);
         }
         ProfScope ps(st, "colsum_db2");
         hipLaunchKernelGGL(colsum_stage2, dim3(D.E, ceil_div(D.d, 256)), dim3(256), 0, st, partial, D.d,
-                           D.E, offsets, db2);
+                           D.E, R, offsets, db2);
         return hipGetLastError();
     }
     {
@@ -347,7 +364,7 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
     ProfScope ps(st, ncols == D.d ? "colsum_db2" : "colsum_db1");
     hipLaunchKernelGGL(colsum_stage1<T>, dim3(max_tiles, cb), dim3(256), 0, st, src, ncols, D.E,
                        offsets, partial);
-    hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, offsets,
+    hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, kColsumRows, offsets,
                        out);
     return hipGetLastError();
 }
