@@ -62,11 +62,12 @@ struct GemmArgs {
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// r = 1 / (1 + exp(2 s)),  s = sqrt(2/pi) (u + 0.044715 u^3):  tanh(s) = 1 - 2 r
+// r = 1 / (1 + exp(2 s)),  s = sqrt(2/pi) (u + 0.044715 u^3):  tanh(s) = 1 - 2 r.
+// exp(2 s) = 2^(u (k1 + k3 u^2)) with log2(e) folded into the two constants.
 __device__ __forceinline__ float gelu_r(float u) {
-    const float u2 = u * u;
-    const float s2 = u * (2.f * HEXA_GELU_C + 2.f * HEXA_GELU_C * HEXA_GELU_A * u2);  // 2 s
-    return fast_rcp(1.f + fast_exp2(s2 * 1.4426950408889634f));
+    constexpr float k1 = 2.f * HEXA_GELU_C * 1.4426950408889634f;
+    constexpr float k3 = k1 * HEXA_GELU_A;
+    return fast_rcp(1.f + fast_exp2(u * (k1 + k3 * (u * u))));
 }
 __device__ __forceinline__ float gelu_fast(float u) { return u - u * gelu_r(u); }
 __device__ __forceinline__ float gelu_grad_fast(float u) {
