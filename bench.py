@@ -27,8 +27,8 @@ METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
 GEMM_LABELS = ("fc1", "fc2", "dgrad2", "dgrad1", "wgrad2", "wgrad1")
 # HBM-side bytes per launch at C5 from rocprofv3 (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 after calibration
 # with a plain 1 GiB copy; profiles/c5_gemm_pmc_counters.md).  Only meaningful for --workload C5.
-TRAFFIC_BYTES = {"fc1": 26.6e9, "fc2": 21.4e9, "dgrad2": 27.1e9, "dgrad1": 23.4e9, "wgrad2": 17.2e9,
-                 "wgrad1": 17.8e9}
+TRAFFIC_BYTES = {"fc1": 24.1e9, "fc2": 16.0e9, "dgrad2": 26.0e9, "dgrad1": 17.2e9, "wgrad2": 17.2e9,
+                 "wgrad1": 21.4e9}
 
 
 def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
