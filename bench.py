@@ -8,6 +8,8 @@ synthetic batch that is already resident in HBM.  Prints ONE JSON line.
   roofline  the slowest kernel of the step (always one of the six bf16 MFMA contractions):
             its 2*A*d*f FLOP over its average launch duration, measured with HIP events that the
             library records on the launch stream, against the 2.5 PFLOP/s dense bf16 MFMA peak
+            (sustained_mfma_peak: a register-only MFMA loop timed in the same run, i.e. the
+            matrix rate at the clock the power limit allows)
   cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample of the same workload
 """
 import argparse
@@ -67,8 +69,8 @@ def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--routing", default=None, help="override the routing recipe (zipf, forced, ...)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -121,6 +123,16 @@ def main():
     prof = B.profile_read()
     B.profile_enable(False)
 
+    # the matrix rate the part sustains under its power limit: a register-only MFMA loop, ~50 ms
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    B.mfma_probe(1024, 2000, sink)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_flop = B.mfma_probe(1024, 30000, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    sustained = probe_flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = w.useful_flop / (ms_per_step * 1e-3) / 1e12
     kernels = {k: {"ms": v[0] / v[1], "launches": v[1]} for k, v in prof.items()}
@@ -128,6 +140,10 @@ def main():
     dom = max((k for k in kernels if k in GEMM_LABELS), key=lambda k: kernels[k]["ms"])
     achieved = gemm_flop / (kernels[dom]["ms"] * 1e-3) / 1e12
     counts = idx["counts"].cpu().numpy()
+    ksum = lambda names: sum(kernels[k]["ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
+    idx_ms = ksum(["index_count", "index_scan", "index_scatter"])
+    fwd_ms = ksum(["fc1", "fc2", "combine_y"]) + 0.5 * ksum(["worklists"])
+    all_ms = ksum(list(kernels))
     out = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -141,7 +157,12 @@ def main():
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16<{dom}>", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom) if w.name == "C5" and not args.routing else None,
-                     "flop_per_launch": gemm_flop, "avg_ms": kernels[dom]["ms"]},
+                     "flop_per_launch": gemm_flop, "avg_ms": kernels[dom]["ms"],
+                     "sustained_mfma_peak": sustained, "frac_of_sustained": achieved / sustained},
+        # sums of kernel durations per step (HIP events); "fwd_incl_index" = index + fwd
+        "phases_ms": {"index": round(idx_ms, 4), "fwd": round(fwd_ms, 4),
+                      "fwd_incl_index": round(idx_ms + fwd_ms, 4),
+                      "bwd": round(all_ms - idx_ms - fwd_ms, 4)},
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
     }
     if not args.no_cpu_baseline:

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 HEXA_F32, HEXA_BF16 = 0, 1
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
            "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
-           "hexa_moe_profile_read")
+           "hexa_moe_profile_read", "hexa_moe_mfma_probe")
 
 
 class Shape(ctypes.Structure):
@@ -49,6 +49,8 @@ def _load():
     lib.hexa_moe_fwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, P, Idx, P, P, S, P]
     lib.hexa_moe_bwd.restype = ctypes.c_int
     lib.hexa_moe_bwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, Idx, P, S, P, P, P, P, P, P, P]
+    lib.hexa_moe_mfma_probe.restype = ctypes.c_int
+    lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
     lib.hexa_moe_profile_enable.restype = None
     lib.hexa_moe_profile_enable.argtypes = [ctypes.c_int]
     lib.hexa_moe_profile_read.restype = ctypes.c_int
@@ -198,3 +200,11 @@ def profile_read() -> Dict[str, Tuple[float, int]]:
         out[label.value.decode()] = (ms.value, n.value)
         i += 1
     return out
+
+
+def mfma_probe(workgroups: int, iters: int, sink: "torch.Tensor") -> float:
+    """Enqueue the register-only MFMA loop on the current stream; returns its FLOP count."""
+    flop = ctypes.c_double()
+    _check(lib.hexa_moe_mfma_probe(int(workgroups), int(iters), _ptr(sink, (1,), torch.float32, "sink"),
+                                   _stream(), ctypes.byref(flop)))
+    return flop.value

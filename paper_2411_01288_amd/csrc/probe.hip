@@ -1,0 +1,47 @@
+// Benchmark helper: a register-only bf16 MFMA loop, to measure the matrix rate the part sustains
+// at the clock its power limit allows (the ceiling the contraction kernels are compared with,
+// next to the nominal 2.5 PFLOP/s).  Not part of the layer.
+#include "common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Every wavefront issues iters * 16 MFMAs (32x32x16, 32 768 FLOP each) on four independent
+// accumulators; operands never leave registers.  The result is written only if it is NaN, which
+// the chosen operands cannot produce: the store keeps the loop alive, nothing more.
+__global__ __launch_bounds__(256) void mfma_probe(int iters, float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.001f * (float)((lane + i) & 7));
+        b[i] = (__bf16)(0.002f * (float)((lane * 3 + i) & 7));
+    }
+    f32x16 c0 = {}, c1 = {}, c2 = {}, c3 = {};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b, c3, 0, 0, 0);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s != s) sink[0] = s;
+}
+
+}  // namespace
+
+extern "C" hexa_status hexa_moe_mfma_probe(int32_t workgroups, int32_t iters, float* sink, void* stream,
+                                           double* flop) {
+    if (!sink || !flop) return HEXA_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0) return HEXA_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_probe, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, iters, sink);
+    *flop = (double)workgroups * 4.0 * (double)iters * 16.0 * 32768.0;
+    return hipGetLastError() == hipSuccess ? HEXA_OK : HEXA_ERR_DEVICE;
+}
