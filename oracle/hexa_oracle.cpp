@@ -25,10 +25,13 @@
 //     index and such experts get exact zero gradients.
 //   * top-k is one index over the T*k (token, slot) pairs instead of k
 //     separate re-index vectors: same sums.
+//   * the router (which the paper takes as given) is top-k by logit with ties
+//     to the lower expert id and softmax gates; see hexa_oracle_route.
 //
 // Pins (tests/test_oracle_pins.py): dense all-experts-then-mask brute force in
 // numpy, central finite differences of every input, the E=1 case against a
-// library 2-layer MLP, structural invariants.  No function here is unpinned.
+// library 2-layer MLP, structural invariants; the router against a stable
+// library sort and a library softmax.  No function here is unpinned.
 //
 // All pointers are host memory, dense row-major.  Inputs are float (bf16
 // workloads pass their values widened, which is exact); every sum runs in
@@ -264,6 +267,41 @@ int hexa_oracle_bwd_experts(int T, int d, int f, int E, int k, const float* x,
                 for (int c = 0; c < nc; ++c) row[c] += xi * dpre[c];
             }
         }
+    }
+    return 0;
+}
+
+// Router front-end: the step that produces the routing choice R_j(x) the
+// paper's operators take as given (Sec. 3.1; App. B Table 5 writes it
+// {R_i(x)}, i < k).  The paper does not define it; the reading here is the
+// one the workload recipes use: per token the k largest of E logits, equal
+// logits resolved towards the lower expert id, slots in descending order of
+// logit; gate weights = softmax over the k selected logits (mode 0) or the
+// softmax over all E logits evaluated at the selected ones (mode 1).
+// Selection is by comparison only (no arithmetic); gates in double.
+// Returns 0, or 1 on bad arguments (k > E, non-finite logits).
+int hexa_oracle_route(int T, int E, int k, int mode, const float* logits, int32_t* topk_idx,
+                      double* gate) {
+    if (T <= 0 || E <= 0 || k <= 0 || k > E || (mode != 0 && mode != 1)) return 1;
+    for (size_t i = 0; i < (size_t)T * E; ++i)
+        if (!std::isfinite(logits[i])) return 1;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float* l = logits + (size_t)t * E;
+        std::vector<char> taken(E, 0);
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < E; ++e)          // ascending e: a later equal logit never wins
+                if (!taken[e] && (best < 0 || l[e] > l[best])) best = e;
+            taken[best] = 1;
+            topk_idx[(size_t)t * k + j] = best;
+        }
+        const double m = (double)l[topk_idx[(size_t)t * k]];   // the largest logit of the row
+        double den = 0.0;
+        if (mode == 0) for (int j = 0; j < k; ++j) den += std::exp((double)l[topk_idx[(size_t)t * k + j]] - m);
+        else           for (int e = 0; e < E; ++e) den += std::exp((double)l[e] - m);
+        for (int j = 0; j < k; ++j)
+            gate[(size_t)t * k + j] = std::exp((double)l[topk_idx[(size_t)t * k + j]] - m) / den;
     }
     return 0;
 }

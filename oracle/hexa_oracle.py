@@ -138,6 +138,21 @@ def bwd_experts(x, topk_idx, gate, W1, b1, W2, dY, experts=None, cols=None):
     return dW1, db1, dW2, db2
 
 
+def route(logits, k, mode=0):
+    """(topk_idx [T,k] int32, gate [T,k] fp64): k largest logits per row, ties to the lower
+    expert id, slots by descending logit; mode 0 = softmax over the selected logits, mode 1 =
+    softmax over all E evaluated at the selected ones."""
+    l, pl = _f32(logits)
+    T, E = l.shape
+    idx = np.empty((T, k), np.int32)
+    gate = np.empty((T, k), np.float64)
+    rc = lib().hexa_oracle_route(_I(T), _I(E), _I(k), _I(mode), pl, idx.ctypes.data_as(_P),
+                                 gate.ctypes.data_as(_P))
+    if rc:
+        raise ValueError("oracle route: bad arguments (k > E, or non-finite logits)")
+    return idx, gate
+
+
 def gelu(u: float) -> float:
     return lib().hexa_oracle_gelu(float(u))
 

@@ -311,3 +311,63 @@ def test_gelu_values_and_derivative(oracle):
         fd = (oracle.gelu(-u + e) - oracle.gelu(-u - e)) / (2 * e)
         assert abs(fd - oracle.gelu_grad(-u)) < 1e-9
     assert abs(oracle.gelu(30.0) - 30.0) < 1e-12 and abs(oracle.gelu(-30.0)) < 1e-12
+
+
+# --------------------------------------------------------------------- router
+# The paper takes the routing choice as given; the reading pinned here: k largest logits, equal
+# logits to the lower expert id, slots by descending logit, softmax gates.
+def _route_ref(logits, k, mode):
+    """numpy / scipy only: a stable sort of the negated logits gives exactly that order."""
+    from scipy.special import softmax
+    order = np.argsort(-logits.astype(np.float64), axis=1, kind="stable")[:, :k]
+    sel = np.take_along_axis(logits.astype(np.float64), order, axis=1)
+    if mode == 0:
+        gate = softmax(sel, axis=1)
+    else:
+        gate = np.take_along_axis(softmax(logits.astype(np.float64), axis=1), order, axis=1)
+    return order.astype(np.int32), gate
+
+
+@pytest.mark.parametrize("T,E,k", [(64, 4, 1), (200, 8, 2), (50, 64, 2), (33, 100, 8), (7, 5, 5)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_route_matches_stable_sort_and_library_softmax(oracle, T, E, k, mode):
+    rng = np.random.default_rng(100 + T + E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    idx, gate = oracle.route(logits, k, mode)
+    ridx, rgate = _route_ref(logits, k, mode)
+    assert np.array_equal(idx, ridx)
+    assert np.abs(gate - rgate).max() < 1e-14
+
+
+def test_route_ties_go_to_the_lower_expert_id(oracle):
+    rng = np.random.default_rng(7)
+    logits = rng.integers(-2, 3, size=(300, 12)).astype(np.float32)   # many equal logits
+    for k in (1, 3, 12):
+        idx, gate = oracle.route(logits, k, 0)
+        ridx, rgate = _route_ref(logits, k, 0)
+        assert np.array_equal(idx, ridx)
+        assert np.abs(gate - rgate).max() < 1e-14
+    row = np.array([[1, 5, 5, 0, 5]], np.float32)
+    idx, gate = oracle.route(row, 3, 0)
+    assert idx.tolist() == [[1, 2, 4]] and np.allclose(gate, 1 / 3, atol=1e-15)
+
+
+def test_route_invariants(oracle):
+    rng = np.random.default_rng(8)
+    logits = (3 * rng.standard_normal((128, 16))).astype(np.float32)
+    idx, g0 = oracle.route(logits, 4, 0)
+    _, g1 = oracle.route(logits, 4, 1)
+    assert np.abs(g0.sum(1) - 1).max() < 1e-14                      # renormalised over the selection
+    assert (np.diff(g0, axis=1) <= 0).all() and (g1.sum(1) < 1).all()
+    assert np.abs(g1 / g1.sum(1, keepdims=True) - g0).max() < 1e-14  # same ratios in both modes
+    assert all(len(set(r)) == 4 for r in idx.tolist())               # k distinct experts
+    ia, ga = oracle.route(logits, 16, 0)                             # k = E: the full softmax, sorted
+    _, gb = oracle.route(logits, 16, 1)
+    assert np.abs(ga - gb).max() < 1e-14
+    shifted, gs = oracle.route(logits + np.float32(8.0), 4, 0)       # exactly representable shift
+    assert np.array_equal(shifted, idx) and np.abs(gs - g0).max() < 1e-6
+    with pytest.raises(ValueError):
+        oracle.route(logits, 17, 0)
+    bad = logits.copy(); bad[3, 2] = np.nan
+    with pytest.raises(ValueError):
+        oracle.route(bad, 2, 0)
