@@ -133,6 +133,18 @@ def main():
     torch.cuda.synchronize()
     sustained = probe_flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
+    # the router front-end (the step before the path; not part of `value`): HBM-bound,
+    # T*E*4 bytes of logits in, T*k*8 bytes out
+    logits = torch.randn((w.T, w.E), dtype=torch.float32, device=dev)
+    rt_idx, rt_gate = B.hexa_moe_route(shape, logits)
+    e0.record()
+    for _ in range(10):
+        B.hexa_moe_route(shape, logits, B.GATE_SOFTMAX_SELECTED, rt_idx, rt_gate)
+    e1.record()
+    torch.cuda.synchronize()
+    route_ms = e0.elapsed_time(e1) / 10
+    route_bytes = w.T * w.E * 4 + w.T * w.k * 8
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = w.useful_flop / (ms_per_step * 1e-3) / 1e12
     kernels = {k: {"ms": v[0] / v[1], "launches": v[1]} for k, v in prof.items()}
@@ -164,6 +176,9 @@ def main():
                       "fwd_incl_index": round(idx_ms + fwd_ms, 4),
                       "bwd": round(all_ms - idx_ms - fwd_ms, 4)},
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
+        "router": {"bound": "hbm", "ms": round(route_ms, 4), "achieved": route_bytes / (route_ms * 1e-3) / 1e9,
+                   "peak": 8000.0, "unit": "GB/s", "frac": route_bytes / (route_ms * 1e-3) / 1e9 / 8000.0,
+                   "bytes": route_bytes},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, data)

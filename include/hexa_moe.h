@@ -134,6 +134,22 @@ HEXA_API hexa_status hexa_moe_bwd(const hexa_moe_shape *shape, const void *dY, c
                          size_t workspace_bytes, void *dx, float *dW1, float *db1, float *dW2,
                          float *db2, float *dgate, void *stream);
 
+/* Router front-end: the step before hexa_moe_index.  The paper takes the routing choice
+ * {R_j(x)} as given (Sec. 3.1; App. B Table 5); this entry point produces it from router logits:
+ * per token the k largest of E logits, equal logits to the lower expert id, slot j = the j-th
+ * largest; gate weights per gate_mode.  Its outputs are what hexa_moe_index / fwd / bwd take.
+ *   logits   [T,E] float  dev, in   (finite; a NaN is treated as -inf and makes that row's gates NaN)
+ *   topk_idx [T,k] int32  dev, out  bit-exact (comparisons only)
+ *   gate     [T,k] float  dev, out
+ * shape: T, E, k are used (d_model, d_ff, dtype ignored).  k <= min(E, 64), E <= 1024, else
+ * HEXA_ERR_UNSUPPORTED / HEXA_ERR_SHAPE. */
+typedef enum {
+    HEXA_GATE_SOFTMAX_SELECTED = 0, /* softmax over the k selected logits (gates sum to 1) */
+    HEXA_GATE_SOFTMAX_ALL = 1       /* softmax over all E logits, evaluated at the selected ones */
+} hexa_gate_mode;
+HEXA_API hexa_status hexa_moe_route(const hexa_moe_shape *shape, const float *logits, int32_t gate_mode,
+                           int32_t *topk_idx, float *gate, void *stream);
+
 /* Per-kernel timing for benchmarks (not part of the layer).  While enabled, every kernel the
  * library launches is bracketed by two HIP events on its stream; enabling (or disabling)
  * discards earlier records.  This is the only part of the library that creates HIP objects.

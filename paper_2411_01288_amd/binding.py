@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 HEXA_F32, HEXA_BF16 = 0, 1
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
            "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
-           "hexa_moe_profile_read", "hexa_moe_mfma_probe")
+           "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route")
 
 
 class Shape(ctypes.Structure):
@@ -51,6 +51,8 @@ def _load():
     lib.hexa_moe_bwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, Idx, P, S, P, P, P, P, P, P, P]
     lib.hexa_moe_mfma_probe.restype = ctypes.c_int
     lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
+    lib.hexa_moe_route.restype = ctypes.c_int
+    lib.hexa_moe_route.argtypes = [ctypes.POINTER(Shape), P, ctypes.c_int32, P, P, P]
     lib.hexa_moe_profile_enable.restype = None
     lib.hexa_moe_profile_enable.argtypes = [ctypes.c_int]
     lib.hexa_moe_profile_read.restype = ctypes.c_int
@@ -208,3 +210,20 @@ def mfma_probe(workgroups: int, iters: int, sink: "torch.Tensor") -> float:
     _check(lib.hexa_moe_mfma_probe(int(workgroups), int(iters), _ptr(sink, (1,), torch.float32, "sink"),
                                    _stream(), ctypes.byref(flop)))
     return flop.value
+
+
+GATE_SOFTMAX_SELECTED, GATE_SOFTMAX_ALL = 0, 1
+
+
+def hexa_moe_route(shape: Shape, logits: torch.Tensor, gate_mode: int = GATE_SOFTMAX_SELECTED,
+                   topk_idx: Optional[torch.Tensor] = None, gate: Optional[torch.Tensor] = None):
+    """Router front-end: (topk_idx [T,k] int32, gate [T,k] float32) from logits [T,E] float32."""
+    dev = logits.device
+    if topk_idx is None:
+        topk_idx = torch.empty((shape.T, shape.k), dtype=torch.int32, device=dev)
+    if gate is None:
+        gate = torch.empty((shape.T, shape.k), dtype=torch.float32, device=dev)
+    _check(lib.hexa_moe_route(ctypes.byref(shape), _ptr(logits, (shape.T, shape.E), torch.float32, "logits"),
+                              int(gate_mode), _ptr(topk_idx, (shape.T, shape.k), torch.int32, "topk_idx"),
+                              _ptr(gate, (shape.T, shape.k), torch.float32, "gate"), _stream()))
+    return topk_idx, gate

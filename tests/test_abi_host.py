@@ -66,6 +66,16 @@ def test_error_codes_without_touching_a_gpu(B):
                             fake, fake, fake, fake, None, None) == 4
     assert lib.hexa_moe_fwd(ctypes.byref(ok), None, fake, fake, fake, fake, fake, fake, idx, fake,
                             fake, 1 << 40, None) == 1
+    # router front-end: k > E and k > 64 are unsupported, E > 1024 is a shape error
+    assert lib.hexa_moe_route(None, fake, 0, fake, fake, None) == 1
+    assert lib.hexa_moe_route(ctypes.byref(ok), None, 0, fake, fake, None) == 1
+    assert lib.hexa_moe_route(ctypes.byref(B.make_shape(8, 64, 64, 4, 5, "bf16")), fake, 0, fake, fake, None) == 3
+    assert lib.hexa_moe_route(ctypes.byref(B.make_shape(8, 64, 64, 128, 65, "bf16")), fake, 0, fake, fake, None) == 3
+    assert lib.hexa_moe_route(ctypes.byref(ok), fake, 2, fake, fake, None) == 3
+    assert lib.hexa_moe_route(ctypes.byref(B.make_shape(8, 64, 64, 2000, 2, "bf16")), fake, 0, fake, fake, None) == 2
+    flop = ctypes.c_double()
+    assert lib.hexa_moe_mfma_probe(0, 10, fake, None, ctypes.byref(flop)) == 2
+    assert lib.hexa_moe_mfma_probe(4, 10, None, None, ctypes.byref(flop)) == 1
     for code in range(6):
         assert lib.hexa_moe_status_string(code)
     assert b"unknown" in lib.hexa_moe_status_string(99)
