@@ -448,19 +448,23 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
     static_assert(NRD <= NM, "fragment reads must fit the substep");
     static_assert(SPS == 4, "the schedule below is written for four k-substeps per block");
     constexpr int NIA = SA::NI, NIB = SB::NI;    // staging instructions per wave, operand and block
-    constexpr int ASTR = 2 * NM / NIA, BSTR = NM / NIB;   // issue-slot strides of the two operands
-    static_assert((2 * NM) % NIA == 0 && NM % NIB == 0, "staging instructions must divide the issue slots");
+    constexpr int ASTR = 2 * NM / NIA;           // issue-slot stride of operand A over substeps 0-1
+    static_assert((2 * NM) % NIA == 0 && NIB <= NM, "staging instructions must fit the issue slots");
     // staging instruction of A for global slot g_ (0 .. 2*NM-1, substeps 0 and 1): every (2*NM/NIA)-th slot
 #define ISSUE_A_AT(g_, buf_, kt_)                                                                \
     do {                                                                                         \
         _Pragma("unroll") for (int o = 0; o < NIA; ++o)                                          \
             if (o * ASTR == (g_)) ISSUE_A(buf_, kt_, o);                               \
     } while (0)
-    // staging instruction of B for slot m_ (0 .. NM-1, substep 3): every (NM/NIB)-th slot
+    // staging instruction of B for slot m_ (0 .. NM-1, substep 3): slots BSKIP, BSKIP+1, ...  The
+    // first slots after the barrier stay free so that a write into the slot block j's A image
+    // leaves can only land (>= 250 cycles of L2 latency later) well after the other waves' last
+    // fragment reads of that image, issued before the barrier, have drained from the LDS queue.
+    constexpr int BSKIP = NM - NIB < 4 ? NM - NIB : 4;
 #define ISSUE_B_AT(m_, buf_, kt_)                                                                \
     do {                                                                                         \
         _Pragma("unroll") for (int o = 0; o < NIB; ++o)                                          \
-            if (o * BSTR == (m_)) ISSUE_B(buf_, kt_, o);                                   \
+            if (o + BSKIP == (m_)) ISSUE_B(buf_, kt_, o);                                        \
     } while (0)
     // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
     // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
