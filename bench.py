@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--routing", default=None, help="override the routing recipe (zipf, forced, ...)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of the step captured into one HIP graph (launch-latency regime: "
+                         "small workloads); per-kernel events are then taken from an eager pass")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -113,15 +116,40 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = B.profile_read()
-    B.profile_enable(False)
+    if args.graph:
+        B.profile_enable(True)      # per-kernel figures from eager steps, outside the timed region
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof = B.profile_read()
+        B.profile_enable(False)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        B.profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        prof = B.profile_read()
+        B.profile_enable(False)
 
     # the matrix rate the part sustains under its power limit: a register-only MFMA loop, ~50 ms
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -161,6 +189,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "pct_of_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{w.name}: one MoE FFN layer fwd+bwd incl. index build, T={w.T} "
                                f"d_model={w.d_model} d_ff={w.d_ff} E={w.E} top-{w.k}, routing={w.routing}",
                    "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
