@@ -26,11 +26,13 @@ sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0
 METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
-GEMM_LABELS = ("fc1", "fc2", "dgrad2", "dgrad1", "wgrad2", "wgrad1")
+# contraction launches: label -> number of 2*A*d*f contractions in the launch (the backward of each
+# linear layer runs its input-gradient and weight-gradient contractions in one grid)
+GEMM_LABELS = {"fc1": 1, "fc2": 1, "dgrad2": 1, "dgrad1": 1, "wgrad2": 1, "wgrad1": 1, "bwd_fc2": 2, "bwd_fc1": 2}
 # HBM-side bytes per launch at C5 from rocprofv3 (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 after calibration
 # with a plain 1 GiB copy; profiles/c5_gemm_pmc_counters.md).  Only meaningful for --workload C5.
 TRAFFIC_BYTES = {"fc1": 24.1e9, "fc2": 16.0e9, "dgrad2": 26.0e9, "dgrad1": 17.2e9, "wgrad2": 17.2e9,
-                 "wgrad1": 21.4e9}
+                 "wgrad1": 21.4e9, "bwd_fc2": 43.2e9, "bwd_fc1": 38.6e9}
 
 
 def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
@@ -177,7 +179,9 @@ def main():
     tflops = w.useful_flop / (ms_per_step * 1e-3) / 1e12
     kernels = {k: {"ms": v[0] / v[1], "launches": v[1]} for k, v in prof.items()}
     gemm_flop = 2.0 * w.A * w.d_model * w.d_ff
-    dom = max((k for k in kernels if k in GEMM_LABELS), key=lambda k: kernels[k]["ms"])
+    # the dominant kernel: the contraction launch with the lowest rate
+    dom = max((k for k in kernels if k in GEMM_LABELS), key=lambda k: kernels[k]["ms"] / GEMM_LABELS[k])
+    gemm_flop *= GEMM_LABELS[dom]
     achieved = gemm_flop / (kernels[dom]["ms"] * 1e-3) / 1e12
     counts = idx["counts"].cpu().numpy()
     ksum = lambda names: sum(kernels[k]["ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps

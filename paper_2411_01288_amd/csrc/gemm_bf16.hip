@@ -1,6 +1,7 @@
 // bf16 MFMA contractions of the expert-specific MoE layer (HEXA-MoE Sec. 3.1; App. B Table 5).
 //
-// Six contractions share one kernel template:
+// Six contractions share one tile routine (forward: one grid each; backward: the input-gradient
+// and weight-gradient contractions of a linear layer share a grid):
 //   row GEMMs  (ESMM, App. B Alg. 2): rows are one expert segment of the re-index vector
 //       FC1     pre = x[perm/k] W1[e] + b1[e],  h = GELU(pre)        K = d, N = f
 //       FC2     o   = h W2[e] + b2[e]   (stored as bf16)                 K = f, N = d
@@ -241,8 +242,9 @@ __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restric
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
+// One work-item slot `item` (slot i is dispatched to XCD i % 8) of contraction OP.
 template <int BM, int BN, int WM, int WN, int OP>
-__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int FM = TM / 32, FN = TN / 32;
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
             // the 8 XCDs work on neighbouring row tiles (mostly one expert) at any time
             const int per_group = kGroupM * tn;
             const int ngroups = ceil_div(tm_total, kGroupM);
-            const int xcd = blockIdx.x % kXcds, loc = blockIdx.x / kXcds;
+            const int xcd = item % kXcds, loc = item / kXcds;
             const int group = (loc / per_group) * kXcds + xcd;
             const int within = loc % per_group;
             if (group >= ngroups) return;
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
         const int tm = ceil_div(g.M, BM), tn = ceil_div(g.N, BN);
         const int tmn = tm * tn;
         const int per = ceil_div(tmn, kXcds);
-        const int xcd = blockIdx.x % kXcds, loc = blockIdx.x / kXcds;
+        const int xcd = item % kXcds, loc = item / kXcds;
         const int tile = xcd * per + loc % per;
         if (tile >= tmn) return;
         if (loc / per >= g.worklist[1]) return;
@@ -681,6 +683,22 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 #undef STORE16
 }
 
+template <int BM, int BN, int WM, int WN, int OP>
+__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
+    gemm_tile<BM, BN, WM, WN, OP>(g, (int)blockIdx.x);
+}
+
+// Two independent contractions in one grid (the paper's fused backward kernel, Sec. 3.2 "Fused
+// Kernel in Backward Propagation": the input gradient and the weight gradient of one linear layer
+// do not depend on each other): slots [0, items_a) are contraction OPA's, the rest OPB's, so the
+// tail of one fills with tiles of the other.  items_a is a multiple of 8 (XCD mapping).
+template <int BM, int BN, int WM, int WN, int OPA, int OPB>
+__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_pair(GemmArgs ga, GemmArgs gb, int items_a) {
+    const int item = (int)blockIdx.x;
+    if (item < items_a) gemm_tile<BM, BN, WM, WN, OPA>(ga, item);
+    else gemm_tile<BM, BN, WM, WN, OPB>(gb, item - items_a);
+}
+
 // Second stage of the split token contraction, plus exact zeros for experts without tokens.
 // out[e] = sum_c kpart[slot_e + c] in chunk order when the expert was split; untouched when it
 // had exactly one chunk (the GEMM wrote it directly).
@@ -726,10 +744,12 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
 }
 
-template <int BM, int BN, int WM, int WN, int OP>
-void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label,
-                   const char* label_fin) {
-    auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
+// Row GEMM OPA and token contraction OPB of one linear layer's backward in one grid, then the
+// split-K finisher of OPB.
+template <int BM, int BN, int WM, int WN, int OPA, int OPB>
+void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipStream_t st,
+                 const char* label, const char* label_fin) {
+    auto kern = gemm_bf16_pair<BM, BN, WM, WN, OPA, OPB>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
@@ -737,18 +757,19 @@ void launch_tokens(const MoeDims& D, const GemmArgs& g, hipStream_t st, const ch
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_done = true;
     }
-    const int tmn = ceil_div(g.M, BM) * ceil_div(g.N, BN);
-    const int chunks_max = D.A / g.chunk_len + D.E;
-    const int grid = kXcds * ceil_div(tmn, kXcds) * chunks_max;
+    const int tm_max = D.A / BM + D.E;
+    const int items_a = kXcds * ceil_div(ceil_div(tm_max, kGroupM), kXcds) * kGroupM * ceil_div(ga.N, BN);
+    const int tmn = ceil_div(gb.M, BM) * ceil_div(gb.N, BN);
+    const int items_b = kXcds * ceil_div(tmn, kXcds) * (D.A / gb.chunk_len + D.E);
     {
         ProfScope ps(st, label);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+        hipLaunchKernelGGL(kern, dim3(items_a + items_b), dim3(WM * WN * 64), lds, st, ga, gb, items_a);
     }
     ProfScope ps(st, label_fin);
-    const size_t mn = (size_t)g.M * g.N;
+    const size_t mn = (size_t)gb.M * gb.N;
     const int gx = (int)((mn / 4 + 255) / 256 < 1024 ? (mn / 4 + 255) / 256 : 1024);
-    hipLaunchKernelGGL(wgrad_finish, dim3(gx, D.E), dim3(256), 0, st, g.offsets, D.E, g.chunk_len, mn,
-                       g.kpart, reinterpret_cast<float*>(g.out0));
+    hipLaunchKernelGGL(wgrad_finish, dim3(gx, D.E), dim3(256), 0, st, gb.offsets, D.E, gb.chunk_len, mn,
+                       gb.kpart, reinterpret_cast<float*>(gb.out0));
 }
 
 constexpr int TBM = 256, TBN = 256, TWM = 2, TWN = 2;
@@ -812,19 +833,16 @@ hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
     launch_worklists(D, idx, ws, st);
-    // dpre = (do W2^T) * GELU'(pre)
-    g.A = (const bf16_t*)ws.dout; g.B = W2; g.pre_in = (const bf16_t*)ws.pre; g.out0 = ws.dpre;
-    g.colpart = ws.colpart;
-    g.K = D.d; g.N = D.f;
-    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD2>(D, g, st, "dgrad2");
-    // dW2[e] = h^T do
-    g.A = (const bf16_t*)ws.h; g.B = (const bf16_t*)ws.dout; g.out0 = dW2; g.M = D.f; g.N = D.d;
-    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD2>(D, g, st, "wgrad2", "wgrad2_finish");
-    // dxp = dpre W1^T
-    g.A = (const bf16_t*)ws.dpre; g.B = W1; g.out0 = ws.dxp; g.K = D.f; g.N = D.d;
-    launch_rows<TBM, TBN, TWM, TWN, OP_DGRAD1>(D, g, st, "dgrad1");
-    // dW1[e] = xg^T dpre
-    g.A = xg; g.B = (const bf16_t*)ws.dpre; g.out0 = dW1; g.M = D.d; g.N = D.f;
-    launch_tokens<TBM, TBN, TWM, TWN, OP_WGRAD1>(D, g, st, "wgrad1", "wgrad1_finish");
+    // 2nd linear layer: dpre = (do W2^T) * GELU'(pre)  and  dW2[e] = h^T do
+    GemmArgs r = g, t = g;
+    r.A = (const bf16_t*)ws.dout; r.B = W2; r.pre_in = (const bf16_t*)ws.pre; r.out0 = ws.dpre;
+    r.colpart = ws.colpart; r.K = D.d; r.N = D.f;
+    t.A = (const bf16_t*)ws.h; t.B = (const bf16_t*)ws.dout; t.out0 = dW2; t.M = D.f; t.N = D.d;
+    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD2, OP_WGRAD2>(D, r, t, st, "bwd_fc2", "wgrad2_finish");
+    // 1st linear layer: dxp = dpre W1^T  and  dW1[e] = xg^T dpre
+    r = g; t = g;
+    r.A = (const bf16_t*)ws.dpre; r.B = W1; r.out0 = ws.dxp; r.K = D.f; r.N = D.d;
+    t.A = xg; t.B = (const bf16_t*)ws.dpre; t.out0 = dW1; t.M = D.d; t.N = D.f;
+    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD1, OP_WGRAD1>(D, r, t, st, "bwd_fc1", "wgrad1_finish");
     return hipGetLastError();
 }
