@@ -150,6 +150,18 @@ typedef enum {
 HEXA_API hexa_status hexa_moe_route(const hexa_moe_shape *shape, const float *logits, int32_t gate_mode,
                            int32_t *topk_idx, float *gate, void *stream);
 
+/* Heterogeneous-aware allocation (Sec. 3.4, Eq. 1 and Eq. 2), a host-only helper: splits `total`
+ * units of work (the global batch for the data-centric setting, Eq. 1; the FFN hidden size for the
+ * model-centric one, Eq. 2) over n devices in proportion to 1 / latency[i], where latency[i] > 0 is
+ * device i's measured time on a common benchmark task.  Shares are multiples of `granule` (>= 1; the
+ * bf16 path of this library needs hidden-size shares that are multiples of 64) and sum to `total`
+ * exactly: every device gets the floor of its ideal share in granules and the granules left over go to
+ * the largest fractional parts (ties to the lower device index), the rounding the paper asks for
+ * without fixing one.  total must be a non-negative multiple of granule.
+ *   latency [n] host, in;  share [n] host, out.  Returns HEXA_ERR_NULL / HEXA_ERR_SHAPE on bad input. */
+HEXA_API hexa_status hexa_moe_allocate(int32_t n, const double *latency, int64_t total, int64_t granule,
+                              int64_t *share);
+
 /* Per-kernel timing for benchmarks (not part of the layer).  While enabled, every kernel the
  * library launches is bracketed by two HIP events on its stream; enabling (or disabling)
  * discards earlier records.  This is the only part of the library that creates HIP objects.

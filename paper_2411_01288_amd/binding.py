@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 HEXA_F32, HEXA_BF16 = 0, 1
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
            "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
-           "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route")
+           "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route",
+           "hexa_moe_allocate")
 
 
 class Shape(ctypes.Structure):
@@ -53,6 +54,9 @@ def _load():
     lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
     lib.hexa_moe_route.restype = ctypes.c_int
     lib.hexa_moe_route.argtypes = [ctypes.POINTER(Shape), P, ctypes.c_int32, P, P, P]
+    lib.hexa_moe_allocate.restype = ctypes.c_int
+    lib.hexa_moe_allocate.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.c_int64,
+                                      ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
     lib.hexa_moe_profile_enable.restype = None
     lib.hexa_moe_profile_enable.argtypes = [ctypes.c_int]
     lib.hexa_moe_profile_read.restype = ctypes.c_int
@@ -227,3 +231,12 @@ def hexa_moe_route(shape: Shape, logits: torch.Tensor, gate_mode: int = GATE_SOF
                               int(gate_mode), _ptr(topk_idx, (shape.T, shape.k), torch.int32, "topk_idx"),
                               _ptr(gate, (shape.T, shape.k), torch.float32, "gate"), _stream()))
     return topk_idx, gate
+
+
+def allocate(latency, total: int, granule: int = 1):
+    """Shares of `total` proportional to 1 / latency[i] (multiples of granule, exact sum)."""
+    n = len(latency)
+    lat = (ctypes.c_double * n)(*[float(t) for t in latency])
+    out = (ctypes.c_int64 * n)()
+    _check(lib.hexa_moe_allocate(n, lat, int(total), int(granule), out))
+    return list(out)

@@ -93,6 +93,39 @@ hexa_status dev(hipError_t e) { return e == hipSuccess ? HEXA_OK : HEXA_ERR_DEVI
 
 extern "C" {
 
+hexa_status hexa_moe_allocate(int32_t n, const double* latency, int64_t total, int64_t granule,
+                              int64_t* share) {
+    if (!latency || !share) return HEXA_ERR_NULL;
+    if (n <= 0 || granule <= 0 || total < 0 || total % granule != 0) return HEXA_ERR_SHAPE;
+    double wsum = 0.0;
+    for (int i = 0; i < n; ++i) {
+        if (!(latency[i] > 0.0) || latency[i] > 1e300) return HEXA_ERR_SHAPE;
+        wsum += 1.0 / latency[i];
+    }
+    const int64_t units = total / granule;
+    std::vector<double> frac((size_t)n);
+    int64_t given = 0;
+    for (int i = 0; i < n; ++i) {
+        const double ideal = (1.0 / latency[i]) / wsum * (double)units;
+        int64_t fl = (int64_t)ideal;            // ideal >= 0
+        if (fl > units) fl = units;
+        frac[(size_t)i] = ideal - (double)fl;
+        share[i] = fl;
+        given += fl;
+    }
+    // hand the remaining granules to the largest fractional parts; on rounding noise that leaves
+    // more than n granules over (it cannot in exact arithmetic), keep cycling
+    for (int64_t left = units - given; left > 0; --left) {
+        int best = 0;
+        for (int i = 1; i < n; ++i)
+            if (frac[(size_t)i] > frac[(size_t)best]) best = i;
+        share[best] += 1;
+        frac[(size_t)best] -= 1.0;
+    }
+    for (int i = 0; i < n; ++i) share[i] *= granule;
+    return HEXA_OK;
+}
+
 size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape* shape) {
     MoeDims D;
     if (check_shape(shape, &D) != HEXA_OK) return 0;

@@ -89,3 +89,23 @@ def test_binding_checks_tensor_shapes_on_the_host(B):
     with pytest.raises(B.HexaError) as ei:
         B._check(3)
     assert ei.value.code == 3
+
+
+def test_heterogeneous_allocation(B):
+    """Eq. 1 / Eq. 2: shares proportional to 1/latency, integral, exact sum."""
+    from fractions import Fraction
+    assert B.allocate([1.0, 1.0, 1.0, 1.0], 128) == [32, 32, 32, 32]
+    assert B.allocate([1.0, 2.0], 90) == [60, 30]                       # twice as fast, twice the batch
+    assert B.allocate([2.0, 1.0, 1.0], 8192, 64) == [1664, 3264, 3264]  # 25.6 / 51.2 / 51.2 granules -> 26 / 51 / 51
+    got = B.allocate([1.0, 1.0, 1.0], 10)
+    assert got == [4, 3, 3]                                             # ties go to the lower device index
+    lat = [0.8, 1.3, 2.9, 1.0, 5.5]
+    for total, g in ((1000, 1), (4096, 64), (40, 8), (0, 1)):
+        s = B.allocate(lat, total, g)
+        assert sum(s) == total and all(v % g == 0 and v >= 0 for v in s)
+        w = [Fraction(1) / Fraction(t) for t in lat]
+        for v, wi in zip(s, w):                                        # within one granule of the ideal share
+            assert abs(Fraction(v) - wi / sum(w) * total) < g
+    for bad in (([1.0, 0.0], 10, 1), ([1.0, -2.0], 10, 1), ([1.0], 10, 3), ([], 10, 1), ([1.0], -1, 1)):
+        with pytest.raises(B.HexaError):
+            B.allocate(*bad)
