@@ -78,8 +78,8 @@ HEXA_API size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape *shape);
 
 /* Bytes of device workspace shared by hexa_moe_fwd and hexa_moe_bwd (0 on an
  * invalid shape).  It holds what the forward pass saves for the backward pass
- * (pre-activations, activations and per-assignment expert outputs, in perm
- * order) plus backward staging.  256-byte alignment of the base is required. */
+ * (pre-activations or the activation's derivative at them, activations and
+ * per-assignment expert outputs, in perm order) plus backward staging.  256-byte alignment of the base is required. */
 HEXA_API size_t hexa_moe_workspace_bytes(const hexa_moe_shape *shape);
 
 HEXA_API const char *hexa_moe_status_string(hexa_status s);
@@ -105,7 +105,7 @@ HEXA_API hexa_status hexa_moe_index(const hexa_moe_shape *shape, const int32_t *
  *   y [T,d]    dev, out, shape.dtype
  *   workspace  dev, >= hexa_moe_workspace_bytes(); afterwards holds the saved
  *              state hexa_moe_bwd reads
- * bf16: products in bf16 MFMA with fp32 accumulation; pre, h and the per-assignment
+ * bf16: products in bf16 MFMA with fp32 accumulation; h, GELU'(pre) and the per-assignment
  * outputs o are stored rounded to bf16 (round-to-nearest-even), the k-slot sum runs
  * in fp32. */
 HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, const int32_t *topk_idx,

@@ -85,7 +85,7 @@ struct MoeDims { int T, d, f, E, k, A; };
 
 // saved + staging regions inside the caller's workspace (device pointers)
 struct MoeWorkspace {
-    void* pre;      // [A,f] elem   pre-activations, perm order        (saved by fwd)
+    void* pre;      // [A,f] elem   fp32: pre-activations; bf16: GELU'(pre), perm order (saved by fwd)
     void* h;        // [A,f] elem   activations, perm order            (saved by fwd)
     void* o;        // [A,d] elem   per-assignment expert outputs      (saved by fwd)
     void* dout;     // [A,d] elem   gate * dY gathered to perm order   (bwd staging)

@@ -3,9 +3,9 @@
 // Six contractions share one tile routine (forward: one grid each; backward: the input-gradient
 // and weight-gradient contractions of a linear layer share a grid):
 //   row GEMMs  (ESMM, App. B Alg. 2): rows are one expert segment of the re-index vector
-//       FC1     pre = x[perm/k] W1[e] + b1[e],  h = GELU(pre)        K = d, N = f
+//       FC1     pre = x[perm/k] W1[e] + b1[e],  h = GELU(pre), g = GELU'(pre) saved   K = d, N = f
 //       FC2     o   = h W2[e] + b2[e]   (stored as bf16)                 K = f, N = d
-//       DGRAD2  dpre = (do W2[e]^T) * GELU'(pre)                     K = d, N = f
+//       DGRAD2  dpre = (do W2[e]^T) * g                              K = d, N = f
 //       DGRAD1  dxp = dpre W1[e]^T      (stored as bf16)                 K = f, N = d
 //   token contractions (ESTMM, App. B Alg. 4): the sum runs over one expert's rows
 //       WGRAD2  dW2[e] = h^T do                                      M = f, N = d
@@ -48,7 +48,7 @@ struct GemmArgs {
     const int32_t* perm;  // FC1 gather
     const int32_t* offsets;
     const bf16_t* bias;   // [E][N] or NULL
-    const bf16_t* pre_in; // DGRAD2
+    const bf16_t* pre_in; // DGRAD2: the saved GELU'(pre)
     void* out0;
     void* out1;
     float* kpart;         // split-K slots [slot][M][N]
@@ -70,12 +70,15 @@ __device__ __forceinline__ float gelu_r(float u) {
     constexpr float k3 = k1 * HEXA_GELU_A;
     return fast_rcp(1.f + fast_exp2(u * (k1 + k3 * (u * u))));
 }
-__device__ __forceinline__ float gelu_fast(float u) { return u - u * gelu_r(u); }
-__device__ __forceinline__ float gelu_grad_fast(float u) {
+// h = GELU(u) = u (1 - r) and g = GELU'(u) = (1 - r) (1 + 2 u r C (1 + 3 A u^2)) from one r
+// (App. B Table 5 rows 2 and 7 need both; the forward epilogue has u in registers, so it saves g
+// for the backward pass instead of u itself: same bytes, and the backward epilogue is one multiply).
+__device__ __forceinline__ void gelu_both(float u, float& h, float& g) {
     const float r = gelu_r(u);
-    const float sig = 1.f - r;  // (1 + tanh) / 2
-    const float q = HEXA_GELU_C * (1.f + 3.f * HEXA_GELU_A * u * u);
-    return sig * (1.f + 2.f * u * r * q);
+    const float ur = u * r;
+    h = u - ur;
+    const float t = 1.f + ur * (2.f * HEXA_GELU_C + 6.f * HEXA_GELU_C * HEXA_GELU_A * (u * u));
+    g = (1.f - r) * t;
 }
 
 // LDS image of a K-contiguous operand: row r = BK*2 bytes = CPRK chunks of 16 bytes (8 bf16 along
@@ -551,7 +554,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // 16 bytes each.  Instead each wave turns one 32-row band (i) at a time through its own 32 KB
     // of the (now idle) stage ring: vectors are written at [row][chunk ^ row] (16-byte chunks, so
     // both directions are conflict-free), read back with a lane per 16-byte chunk of a row, and
-    // leave as full 256- or 512-byte row segments.  DGRAD2's saved pre-activations come in the
+    // leave as full 256- or 512-byte row segments.  DGRAD2's saved activation derivatives come in the
     // same way, staged one band ahead.
     __syncthreads();   // every wave is done reading fragments
 #define STORE16(p_, v_) (*reinterpret_cast<u32x4*>(p_) = (v_))
@@ -564,7 +567,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         static_assert(TN == 128, "epilogue staging is laid out for 128-column wave tiles");
         const size_t ldo = (size_t)g.N;
         const int wrow0 = wm * TM, wcol0 = wn * TN;
-        // DGRAD2: stage pre[band][128 cols] (bf16, 256 B rows, chunk ^ (row & 15)) with direct loads
+        // DGRAD2: stage the saved GELU'(pre)[band][128 cols] (bf16, 256 B rows, chunk ^ (row & 15)) with direct loads
         rsrc_t rp;
         uint32_t pre_voff = 0;
         if constexpr (OP == OP_DGRAD2) {
@@ -616,10 +619,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         const int c = col >> 3;
                         const uint32_t off = (uint32_t)(l32 * RPB + ((c ^ (l32 & (CPRO - 1))) << 4) + hi * 8);
                         if constexpr (OP == OP_FC1) {
+                            float hh[4], gg[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) gelu_both(v[r], hh[r], gg[r]);
                             u32x2 pz, hz;
-                            pz.x = pack_bf2(v[0], v[1]); pz.y = pack_bf2(v[2], v[3]);
-                            hz.x = pack_bf2(gelu_fast(v[0]), gelu_fast(v[1]));
-                            hz.y = pack_bf2(gelu_fast(v[2]), gelu_fast(v[3]));
+                            pz.x = pack_bf2(gg[0], gg[1]); pz.y = pack_bf2(gg[2], gg[3]);
+                            hz.x = pack_bf2(hh[0], hh[1]); hz.y = pack_bf2(hh[2], hh[3]);
                             *reinterpret_cast<u32x2*>(wreg + off) = pz;
                             *reinterpret_cast<u32x2*>(wreg + 8192 + off) = hz;
                         } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
@@ -631,8 +636,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                             const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
                             const float p2 = __uint_as_float(pp.y << 16), p3 = __uint_as_float(pp.y & 0xffff0000u);
                             u32x2 d;
-                            d.x = pack_bf2(v[0] * gelu_grad_fast(p0), v[1] * gelu_grad_fast(p1));
-                            d.y = pack_bf2(v[2] * gelu_grad_fast(p2), v[3] * gelu_grad_fast(p3));
+                            d.x = pack_bf2(v[0] * p0, v[1] * p1);
+                            d.y = pack_bf2(v[2] * p2, v[3] * p3);
                             *reinterpret_cast<u32x2*>(wreg + off) = d;
                         }
                     }
