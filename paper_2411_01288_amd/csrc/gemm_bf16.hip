@@ -136,15 +136,32 @@ __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uin
                  : "memory");
 }
 
+// The same in two parts for the K loop, where the instructions of a staging request are spread over
+// two issue slots: the LDS address (an integer byte address, wave-uniform) goes into M0 in one slot,
+// the load follows in the next one (an MFMA in between provides the wait state).  Nothing else in the
+// K loop uses M0.
+__device__ __forceinline__ void dtl_m0(uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory");
+}
+__device__ __forceinline__ void dtl_load(rsrc_t r, uint32_t voff, uint32_t soff) {
+    asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :
+                 : "v"(voff), "s"(r), "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "memory");
+}
+
 // K-contiguous operand (R rows x BK k, ROWB bytes per row in memory order along k).
 // Instruction q (= wave + NW*i) fills RPQ = 1024/ROWB rows: lane l -> row RPQ*q + l/CPRK,
 // position l%CPRK.
-template <int R, int NW>
+template <int R, int NW, bool GATHER>
 struct StageKC {
     static constexpr int RPQ = 1024 / ROWB;      // rows per instruction
     static constexpr int NI = R / RPQ / NW;      // instructions per wave and stage
     static_assert(R % (RPQ * NW) == 0 && (RPQ * NW) % 16 == 0, "unsupported staging shape");
-    struct Lane { uint32_t voff[NI]; };          // byte offset of (row, chunk) from the resource base
+    // byte offset of (row, chunk) from the resource base: one per instruction when the rows are
+    // gathered; otherwise instruction i is RPQ*NW*i rows further down, which goes into the scalar
+    // offset
+    struct Lane { uint32_t voff[GATHER ? NI : 1]; };
     // chunk this lane must fetch: its position XOR the swizzle key of its row (the key has period
     // 16 rows and RPQ*NW is a multiple of 16, so it is the same for every instruction of a wave)
     __device__ static __forceinline__ int lane_chunk(int wave, int lane) {
@@ -153,9 +170,13 @@ struct StageKC {
     __device__ static __forceinline__ int lane_row(int wave, int lane, int i) {
         return RPQ * (wave + NW * i) + lane / CPRK;
     }
-    __device__ static __forceinline__ void issue(rsrc_t r, uint8_t* stage_base, int wave, uint32_t soff,
-                                                 const Lane& ln, int i) {
-        dtl16(r, stage_base + (wave + NW * i) * 1024, ln.voff[i], soff);
+    // instruction i of this wave: set-up (LDS address of its 1 KB piece of the slot at lds_slot) and load
+    __device__ static __forceinline__ void prep(uint32_t lds_slot, int wave, int i) {
+        dtl_m0(lds_slot + (uint32_t)(wave + NW * i) * 1024u);
+    }
+    __device__ static __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t row_bytes, const Lane& ln, int i) {
+        if constexpr (GATHER) dtl_load(r, ln.voff[i], soff);
+        else dtl_load(r, ln.voff[0], soff + (uint32_t)(RPQ * NW * i) * row_bytes);
     }
 };
 
@@ -178,9 +199,11 @@ struct StageKS {
         const int c = (lane % CPR) ^ ((k & 3) << 2);         // (RPI*NW*i is a multiple of 4)
         return Lane{(uint32_t)k * ld_bytes + (uint32_t)(col0 + 8 * c) * 2u};
     }
-    __device__ static __forceinline__ void issue(rsrc_t r, uint8_t* stage_base, int wave, uint32_t ld_bytes,
-                                                 uint32_t soff, const Lane& ln, int i) {
-        dtl16(r, stage_base + (wave + NW * i) * 1024, ln.voff, soff + (uint32_t)(RPI * NW * i) * ld_bytes);
+    __device__ static __forceinline__ void prep(uint32_t lds_slot, int wave, int i) {
+        dtl_m0(lds_slot + (uint32_t)(wave + NW * i) * 1024u);
+    }
+    __device__ static __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t ld_bytes, const Lane& ln, int i) {
+        dtl_load(r, ln.voff, soff + (uint32_t)(RPI * NW * i) * ld_bytes);
     }
 };
 
@@ -314,8 +337,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 
     // ---- staging set-up -----------------------------------------------------------------------
     constexpr int NW = WM * WN;
-    using SA = typename std::conditional<TOKENS, StageKS<BM, NW>, StageKC<BM, NW>>::type;
-    using SB = typename std::conditional<B_KS, StageKS<BN, NW>, StageKC<BN, NW>>::type;
+    using SA = typename std::conditional<TOKENS, StageKS<BM, NW>, StageKC<BM, NW, OP == OP_FC1>>::type;
+    using SB = typename std::conditional<B_KS, StageKS<BN, NW>, StageKC<BN, NW, false>>::type;
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     typename SA::Lane lna;
     typename SB::Lane lnb;
@@ -329,11 +352,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         else ra = make_rsrc(g.A + (size_t)m0 * g.K, (uint32_t)mvalid * (uint32_t)g.K * 2u);
         a_step = BK * 2;
         const uint32_t ca = (uint32_t)SA::lane_chunk(uwave, lane) * 16u;
+        if constexpr (OP == OP_FC1) {
 #pragma unroll
-        for (int i = 0; i < SA::NI; ++i) {
-            uint32_t r = (uint32_t)SA::lane_row(uwave, lane, i);
-            if constexpr (OP == OP_FC1) r = (uint32_t)(g.perm[m0 + ((int)r < mvalid ? (int)r : 0)] / g.topk);
-            lna.voff[i] = r * (uint32_t)g.K * 2u + ca;
+            for (int i = 0; i < SA::NI; ++i) {
+                const int r = SA::lane_row(uwave, lane, i);
+                lna.voff[i] = (uint32_t)(g.perm[m0 + (r < mvalid ? r : 0)] / g.topk) * (uint32_t)g.K * 2u + ca;
+            }
+        } else {
+            lna.voff[0] = (uint32_t)SA::lane_row(uwave, lane, 0) * (uint32_t)g.K * 2u + ca;
         }
         if constexpr (B_KS) {  // W[e][K][N]
             b_ld = (uint32_t)g.N * 2u;
@@ -344,9 +370,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
             rb = make_rsrc(g.B + ((size_t)e * g.N + n0) * g.K, (uint32_t)nvalid * (uint32_t)g.K * 2u);
             b_step = BK * 2;
             const uint32_t cb = (uint32_t)SB::lane_chunk(uwave, lane) * 16u;
-#pragma unroll
-            for (int i = 0; i < SB::NI; ++i)
-                lnb.voff[i] = (uint32_t)SB::lane_row(uwave, lane, i) * (uint32_t)g.K * 2u + cb;
+            lnb.voff[0] = (uint32_t)SB::lane_row(uwave, lane, 0) * (uint32_t)g.K * 2u + cb;
         }
     } else {
         // both operands are [tokens][features] in perm order; tokens past this item's range fall
@@ -360,17 +384,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
             lnb = SB::lane_init(uwave, lane, b_ld, n0);
         }
     }
-    // one staging instruction of operand A / B for K-step kt_ into LDS stage buffer buf_
-#define ISSUE_A(buf_, kt_, i_)                                                                   \
-    do {                                                                                         \
-        if constexpr (TOKENS) SA::issue(ra, (buf_), uwave, a_ld, (kt_) * a_step, lna, i_);       \
-        else SA::issue(ra, (buf_), uwave, (kt_) * a_step, lna, i_);                              \
-    } while (0)
-#define ISSUE_B(buf_, kt_, i_)                                                                   \
-    do {                                                                                         \
-        if constexpr (B_KS) SB::issue(rb, (buf_), uwave, b_ld, (kt_) * b_step, lnb, i_); \
-        else SB::issue(rb, (buf_), uwave, (kt_) * b_step, lnb, i_);                   \
-    } while (0)
+    // staging instruction i_ of operand A / B for block kt_ into the ring slot at LDS byte address
+    // slot_: set-up part (M0) and load part
+    const uint32_t smem0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
+    const uint32_t a_row = TOKENS ? a_ld : (uint32_t)g.K * 2u, b_row = B_KS ? b_ld : (uint32_t)g.K * 2u;
+#define PREP_A(slot_, i_) SA::prep((slot_), uwave, i_)
+#define PREP_B(slot_, i_) SB::prep((slot_), uwave, i_)
+#define LOAD_A(kt_, i_) SA::load(ra, (kt_) * a_step, a_row, lna, i_)
+#define LOAD_B(kt_, i_) SB::load(rb, (kt_) * b_step, b_row, lnb, i_)
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -453,23 +474,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     static_assert(NRD <= NM, "fragment reads must fit the substep");
     static_assert(SPS == 4, "the schedule below is written for four k-substeps per block");
     constexpr int NIA = SA::NI, NIB = SB::NI;    // staging instructions per wave, operand and block
-    constexpr int ASTR = 2 * NM / NIA;           // issue-slot stride of operand A over substeps 0-1
-    static_assert((2 * NM) % NIA == 0 && NIB <= NM, "staging instructions must fit the issue slots");
-    // staging instruction of A for global slot g_ (0 .. 2*NM-1, substeps 0 and 1): every (2*NM/NIA)-th slot
-#define ISSUE_A_AT(g_, buf_, kt_)                                                                \
+    // A staging request takes two issue slots: its set-up after one MFMA, its load after the next.
+    // Operand A's NIA requests are spread over substeps 0 and 1 (request o: global slots o*ASTR+1,
+    // o*ASTR+2); operand B's NIB requests follow the block barrier in substep 3 (request o: slots
+    // BSKIP + o*BSTR, + 1; with BSTR = 1 a slot holds the load of one request and then the set-up of
+    // the next, which is fine: the load has read M0 by then).  The first slots after the barrier stay free so that a write into the
+    // slot block j's A image leaves can only land (>= 250 cycles of L2 latency later) well after
+    // the other waves' last fragment reads of that image, issued before the barrier, have drained
+    // from the LDS queue.
+    constexpr int ASTR = 2 * NM / NIA;
+    constexpr int BSKIP = 2, BSTR = (NM - BSKIP) / NIB;
+    static_assert((2 * NM) % NIA == 0 && ASTR >= 3 && BSTR >= 1 && BSKIP + BSTR * (NIB - 1) + 1 < NM,
+                  "staging requests must fit the issue slots");
+#define STAGE_A_AT(g_, slot_, kt_)                                                               \
     do {                                                                                         \
-        _Pragma("unroll") for (int o = 0; o < NIA; ++o)                                          \
-            if (o * ASTR == (g_)) ISSUE_A(buf_, kt_, o);                               \
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o) {                                        \
+            if (o * ASTR + 1 == (g_)) PREP_A(slot_, o);                                          \
+            if (o * ASTR + 2 == (g_)) LOAD_A(kt_, o);                                            \
+        }                                                                                        \
     } while (0)
-    // staging instruction of B for slot m_ (0 .. NM-1, substep 3): slots BSKIP, BSKIP+1, ...  The
-    // first slots after the barrier stay free so that a write into the slot block j's A image
-    // leaves can only land (>= 250 cycles of L2 latency later) well after the other waves' last
-    // fragment reads of that image, issued before the barrier, have drained from the LDS queue.
-    constexpr int BSKIP = NM - NIB < 4 ? NM - NIB : 4;
-#define ISSUE_B_AT(m_, buf_, kt_)                                                                \
+#define STAGE_B_AT(m_, slot_, kt_)                                                               \
     do {                                                                                         \
-        _Pragma("unroll") for (int o = 0; o < NIB; ++o)                                          \
-            if (o + BSKIP == (m_)) ISSUE_B(buf_, kt_, o);                                        \
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o) {                                        \
+            if (o * BSTR + BSKIP + 1 == (m_)) LOAD_B(kt_, o);                                    \
+            if (o * BSTR + BSKIP == (m_)) PREP_B(slot_, o);                                      \
+        }                                                                                        \
     } while (0)
     // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
     // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
@@ -507,10 +536,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     const int klast = nk > 0 ? nk - 1 : 0;
     if (nk > 0) {
         const uint32_t k1 = (uint32_t)min(1, klast);
-        _Pragma("unroll") for (int o = 0; o < NIA; ++o) ISSUE_A(smem + 0 * SLOT, 0u, o);
-        _Pragma("unroll") for (int o = 0; o < NIB; ++o) ISSUE_B(smem + 1 * SLOT, 0u, o);
-        _Pragma("unroll") for (int o = 0; o < NIA; ++o) ISSUE_A(smem + 2 * SLOT, k1, o);
-        _Pragma("unroll") for (int o = 0; o < NIB; ++o) ISSUE_B(smem + 3 * SLOT, k1, o);
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 0 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(0u, o); }
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 1 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(0u, o); }
+        _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 2 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(k1, o); }
+        _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 3 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(k1, o); }
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA + NIB) : "memory");
     __syncthreads();
@@ -525,28 +554,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         const int sa2 = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
         uint8_t* anext = smem + sa1 * SLOT;
         uint8_t* bnext = smem + sb1 * SLOT;
-        uint8_t* a2 = smem + sa2 * SLOT;          // A(j+2): the slot of B(j-1)
+        const uint32_t a2 = smem0 + (uint32_t)(sa2 * SLOT);   // A(j+2): the slot of B(j-1)
+        const uint32_t b2 = smem0 + (uint32_t)(sa * SLOT);    // B(j+2): the slot of A(j)
         const uint32_t kreq = (uint32_t)min(j + 2, klast);
         FENCE();
-        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, m), ISSUE_A_AT(m, a2, kreq));
-        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, abase, bbase, 2, m), ISSUE_A_AT(NM + m, a2, kreq));
+        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, m), STAGE_A_AT(m, a2, kreq));
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, abase, bbase, 2, m), STAGE_A_AT(NM + m, a2, kreq));
         SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 3, m), (void)0);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
         __syncthreads();
         FENCE();
-        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, m), ISSUE_B_AT(m, abase, kreq));
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, m), STAGE_B_AT(m, b2, kreq));
         sa = sa1; sb = sb1;
     }
     // no staging write may still be in flight when the workgroup gives its LDS back
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#undef ISSUE_A_AT
-#undef ISSUE_B_AT
+#undef STAGE_A_AT
+#undef STAGE_B_AT
 #undef SUBSTEP
 #undef READ_ONE
 #undef TR_READ
 #undef FENCE
-#undef ISSUE_A
-#undef ISSUE_B
+#undef PREP_A
+#undef PREP_B
+#undef LOAD_A
+#undef LOAD_B
 
     // ---- epilogue ------------------------------------------------------------------------------
     // In block (i, j) a lane holds row i*32 + l32 and, in register quad q, the four columns
