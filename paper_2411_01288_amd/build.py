@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
@@ -14,9 +15,31 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Wno-unused-command-line-argument"]
 
 
+# The contraction kernels count their own direct-to-LDS loads in vmcnt; a register spill inside
+# their K loop would add vector-memory operations the count does not know about.  So the build
+# refuses a gemm_bf16.hip whose kernels use any scratch memory at all.
+NO_SCRATCH = {"gemm_bf16.hip"}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    subprocess.check_call(["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src not in NO_SCRATCH:
+        subprocess.check_call(cmd)
+        return obj
+    res = subprocess.run(cmd + ["-Rpass-analysis=kernel-resource-usage"], stderr=subprocess.PIPE, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {src}:\n{res.stderr}")
+    name, bad = None, []
+    for line in res.stderr.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and int(m.group(1)) > 0 and name and "gemm_bf16" in name:
+            bad.append((name, int(m.group(1))))
+    if bad:
+        raise RuntimeError(f"{src}: kernels spill registers (scratch bytes per lane): {bad}")
     return obj
 
 

@@ -133,7 +133,7 @@ __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uin
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(r), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The same in two parts for the K loop, where the instructions of a staging request are spread over
@@ -141,7 +141,7 @@ __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uin
 // the load follows in the next one (an MFMA in between provides the wait state).  Nothing else in the
 // K loop uses M0.
 __device__ __forceinline__ void dtl_m0(uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory");
+    asm volatile("s_mov_b32 m0, %0" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory", "m0");
 }
 __device__ __forceinline__ void dtl_load(rsrc_t r, uint32_t voff, uint32_t soff) {
     asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
