@@ -69,6 +69,26 @@ def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
     }
 
 
+def hbm_steps(w, kernels, copy_gbps):
+    es = 4 if w.dtype == "f32" else 2
+    A, T, d, k = w.A, w.T, w.d_model, w.k
+    algo = {
+        # y_t = sum_j g o_a: o [A,d] and inv, gate in; y [T,d] out
+        "combine_y": A * d * es + T * d * es + A * 8,
+        # dY (gathered), o, x in; dout, xg out (+ dgate, column-sum partials)
+        "bwd_prologue": A * d * es * (5 if w.dtype != "f32" else 3) + A * 12,
+        "combine_dx": A * d * es + T * d * es + A * 4,
+        "index_scatter": A * 4 + A * 8,
+    }
+    out = {"copy_GBps": round(copy_gbps, 1)}
+    for name, nbytes in algo.items():
+        if name in kernels and kernels[name]["ms"] > 0:
+            gbps = nbytes / (kernels[name]["ms"] * 1e-3) / 1e9
+            out[name] = {"ms": round(kernels[name]["ms"], 4), "bytes": int(nbytes), "GBps": round(gbps, 1),
+                         "frac_of_hbm_peak": round(gbps / 8000.0, 3), "frac_of_copy": round(gbps / copy_gbps, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,6 +196,18 @@ def main():
     route_ms = e0.elapsed_time(e1) / 10
     route_bytes = w.T * w.E * 4 + w.T * w.k * 8
 
+    # plain device copy (1 GiB read + 1 GiB written) as the yardstick for the bandwidth-bound steps
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = w.useful_flop / (ms_per_step * 1e-3) / 1e12
     kernels = {k: {"ms": v[0] / v[1], "launches": v[1]} for k, v in prof.items()}
@@ -212,6 +244,8 @@ def main():
                       "bwd": round(all_ms - idx_ms - fwd_ms, 4)},
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
         "contraction_tflops": {k: round(v, 1) for k, v in rates.items()},
+        # bandwidth-bound steps: algorithmic bytes (each tensor once) over the kernel's duration
+        "hbm_steps": hbm_steps(w, kernels, copy_gbps),
         "router": {"bound": "hbm", "ms": round(route_ms, 4), "achieved": route_bytes / (route_ms * 1e-3) / 1e9,
                    "peak": 8000.0, "unit": "GB/s", "frac": route_bytes / (route_ms * 1e-3) / 1e9 / 8000.0,
                    "bytes": route_bytes},
