@@ -271,6 +271,39 @@ int hexa_oracle_bwd_experts(int T, int d, int f, int E, int k, const float* x,
     return 0;
 }
 
+// The paper's own form of the re-index structures (App. B Alg. 1; Sec. 3.2): every expert's
+// sub-vector is padded with -1 to a multiple of the tile BLK, so v has length N' = sum of the
+// rounded-up counts and idx_[e] is the start of expert e's padded sub-vector, idx_[E] = N'.
+// (The printed listing rounds the counts down and repeats that loop; the text pads up, and only
+// that leaves room for every token -- the reading taken here.)  Inside a sub-vector the ids
+// are ascending (the listing leaves their order to atomics).  Entries are flat assignment ids
+// a = t*k + j; for k = 1 these are the paper's token indices.  v has capacity cap >= N' and every
+// entry past a sub-vector's tokens, including those past N', is -1.
+// Returns 0, or 1 on bad arguments (id out of range, blk < 1, cap < N').
+int hexa_oracle_padded_index(int T, int k, int E, int blk, const int32_t* topk_idx, long long cap,
+                             int32_t* v, int32_t* idx_) {
+    if (T <= 0 || k <= 0 || E <= 0 || blk <= 0) return 1;
+    const long long A = (long long)T * k;
+    std::vector<long long> ctr(E, 0);
+    for (long long a = 0; a < A; ++a) {
+        const int e = topk_idx[a];
+        if (e < 0 || e >= E) return 1;
+        ctr[e] += 1;
+    }
+    long long np = 0;
+    idx_[0] = 0;
+    for (int e = 0; e < E; ++e) {
+        np += (ctr[e] + blk - 1) / blk * blk;       // padded up
+        idx_[e + 1] = (int32_t)np;
+    }
+    if (np > cap) return 1;
+    for (long long i = 0; i < cap; ++i) v[i] = -1;
+    std::vector<long long> pos(E);
+    for (int e = 0; e < E; ++e) pos[e] = idx_[e];
+    for (long long a = 0; a < A; ++a) v[pos[topk_idx[a]]++] = (int32_t)a;   // ascending a
+    return 0;
+}
+
 // Router front-end: the step that produces the routing choice R_j(x) the
 // paper's operators take as given (Sec. 3.1; App. B Table 5 writes it
 // {R_i(x)}, i < k).  The paper does not define it; the reading here is the

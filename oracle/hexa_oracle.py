@@ -138,6 +138,22 @@ def bwd_experts(x, topk_idx, gate, W1, b1, W2, dY, experts=None, cols=None):
     return dW1, db1, dW2, db2
 
 
+def padded_index(topk_idx, E, blk, cap=None):
+    """(v [cap] int32, idx_ [E+1] int32): the paper's -1-padded re-index vector over flat assignment
+    ids and the starts of the padded per-expert sub-vectors; cap defaults to A + E*(blk-1)."""
+    idx, p = _i32(topk_idx)
+    T, k = idx.shape
+    if cap is None:
+        cap = T * k + E * (blk - 1)
+    v = np.empty(cap, np.int32)
+    starts = np.empty(E + 1, np.int32)
+    rc = lib().hexa_oracle_padded_index(_I(T), _I(k), _I(E), _I(blk), p, ctypes.c_longlong(cap),
+                                        v.ctypes.data_as(_P), starts.ctypes.data_as(_P))
+    if rc:
+        raise ValueError("oracle padded_index: bad arguments")
+    return v, starts
+
+
 def route(logits, k, mode=0):
     """(topk_idx [T,k] int32, gate [T,k] fp64): k largest logits per row, ties to the lower
     expert id, slots by descending logit; mode 0 = softmax over the selected logits, mode 1 =

@@ -371,3 +371,44 @@ def test_route_invariants(oracle):
     bad = logits.copy(); bad[3, 2] = np.nan
     with pytest.raises(ValueError):
         oracle.route(bad, 2, 0)
+
+
+# ------------------------------------------------- the paper's padded re-index form
+def test_padded_index_golden_fixture(oracle):
+    """Fig. 3's dimensions (10 tokens, 4 experts, tile 4), routing and expected vectors worked by hand
+    in tests/golden/index_10tok_4exp.txt."""
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "index_10tok_4exp.txt")):
+        tok = line.split("#")[0].split()
+        if tok:
+            vals[tok[0]] = [int(t) for t in tok[1:]]
+    routing = np.array(vals["R"], np.int32).reshape(-1, 1)
+    v, starts = oracle.padded_index(routing, 4, 4)
+    assert starts.tolist() == vals["padded_starts"]
+    assert v[: starts[-1]].tolist() == vals["padded_v"]
+    assert (v[starts[-1]:] == -1).all()
+
+
+@pytest.mark.parametrize("T,k,E,blk", [(10, 1, 4, 4), (200, 2, 7, 16), (33, 3, 5, 1), (64, 1, 3, 64), (5, 2, 9, 8)])
+def test_padded_index_against_brute_force(oracle, T, k, E, blk):
+    rng = np.random.default_rng(T + E + blk)
+    idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    if E > 2:
+        idx[idx == 1] = 0                                   # an empty expert
+    v, starts = oracle.padded_index(idx, E, blk)
+    flat = idx.reshape(-1)
+    exp_v, exp_s = [], [0]
+    for e in range(E):                                      # python lists, no shared code
+        ids = [a for a in range(T * k) if flat[a] == e]
+        pad = (-len(ids)) % blk
+        exp_v += ids + [-1] * pad
+        exp_s.append(len(exp_v))
+    assert starts.tolist() == exp_s
+    assert v[: exp_s[-1]].tolist() == exp_v and (v[exp_s[-1]:] == -1).all()
+    assert all(s % blk == 0 for s in exp_s)                 # every sub-vector is tile-aligned
+    # the unpadded index is the padded one with the -1 entries removed
+    counts, offsets, perm, inv = oracle.index(idx, E)
+    assert v[v >= 0].tolist() == perm.tolist()
+    with pytest.raises(ValueError):
+        oracle.padded_index(idx, E, blk, cap=exp_s[-1] - 1)
