@@ -94,6 +94,20 @@ HEXA_API hexa_status hexa_moe_index(const hexa_moe_shape *shape, const int32_t *
                            hexa_moe_idx out, void *scratch, size_t scratch_bytes,
                            void *stream);
 
+/* The paper's own form of the index (App. B Alg. 1; Sec. 3.2), derived from hexa_moe_index's output
+ * for callers written against it: every expert's sub-vector padded with -1 up to a multiple of the
+ * tile size blk.
+ *   idx      as written by hexa_moe_index (offsets and perm are read)               dev, in
+ *   v        [v_entries] int32, v_entries >= hexa_moe_padded_capacity() = A + E*(blk-1)   dev, out
+ *            expert e's flat assignment ids (ascending; token ids when k = 1) at
+ *            v[idx_pad[e] ...], then -1 up to idx_pad[e+1]; -1 from idx_pad[E] (the paper's N') on
+ *   idx_pad  [E+1] int32: starts of the padded sub-vectors (the paper's idx_)     dev, out
+ * Bit-exact.  (The printed listing rounds the counts down; Sec. 3.2 pads them up, which is what fits
+ * every token, and what is done here.) */
+HEXA_API size_t hexa_moe_padded_capacity(const hexa_moe_shape *shape, int32_t blk);
+HEXA_API hexa_status hexa_moe_padded_index(const hexa_moe_shape *shape, hexa_moe_idx idx, int32_t blk,
+                                  int32_t *v, size_t v_entries, int32_t *idx_pad, void *stream);
+
 /* Forward (App. B Table 5 rows 1-3; ESMM of Sec. 3.1):
  *   pre_a = x_t W1[e_a] + b1[e_a];  h_a = GELU_tanh(pre_a);  o_a = h_a W2[e_a] + b2[e_a]
  *   y_t   = sum_j gate[t,j] * o_{t*k+j}

@@ -20,7 +20,7 @@ HEXA_F32, HEXA_BF16 = 0, 1
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
            "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
            "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route",
-           "hexa_moe_allocate")
+           "hexa_moe_allocate", "hexa_moe_padded_capacity", "hexa_moe_padded_index")
 
 
 class Shape(ctypes.Structure):
@@ -54,6 +54,10 @@ def _load():
     lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
     lib.hexa_moe_route.restype = ctypes.c_int
     lib.hexa_moe_route.argtypes = [ctypes.POINTER(Shape), P, ctypes.c_int32, P, P, P]
+    lib.hexa_moe_padded_capacity.restype = S
+    lib.hexa_moe_padded_capacity.argtypes = [ctypes.POINTER(Shape), ctypes.c_int32]
+    lib.hexa_moe_padded_index.restype = ctypes.c_int
+    lib.hexa_moe_padded_index.argtypes = [ctypes.POINTER(Shape), Idx, ctypes.c_int32, P, S, P, P]
     lib.hexa_moe_allocate.restype = ctypes.c_int
     lib.hexa_moe_allocate.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.c_int64,
                                       ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
@@ -240,3 +244,17 @@ def allocate(latency, total: int, granule: int = 1):
     out = (ctypes.c_int64 * n)()
     _check(lib.hexa_moe_allocate(n, lat, int(total), int(granule), out))
     return list(out)
+
+
+def hexa_moe_padded_index(shape: Shape, idx: Dict[str, torch.Tensor], blk: int):
+    """(v [A + E*(blk-1)] int32, idx_pad [E+1] int32): the paper's -1-padded form of the index."""
+    dev = idx["perm"].device
+    cap = lib.hexa_moe_padded_capacity(ctypes.byref(shape), int(blk))
+    if cap == 0:
+        raise HexaError(2)
+    v = torch.empty(cap, dtype=torch.int32, device=dev)
+    starts = torch.empty(shape.E + 1, dtype=torch.int32, device=dev)
+    _check(lib.hexa_moe_padded_index(ctypes.byref(shape), _idx_struct(shape, idx), int(blk),
+                                     _ptr(v, (cap,), torch.int32, "v"), cap,
+                                     _ptr(starts, (shape.E + 1,), torch.int32, "idx_pad"), _stream()))
+    return v, starts

@@ -93,6 +93,23 @@ hexa_status dev(hipError_t e) { return e == hipSuccess ? HEXA_OK : HEXA_ERR_DEVI
 
 extern "C" {
 
+size_t hexa_moe_padded_capacity(const hexa_moe_shape* shape, int32_t blk) {
+    MoeDims D;
+    if (blk <= 0 || check_shape(shape, &D) != HEXA_OK) return 0;
+    return (size_t)D.A + (size_t)D.E * (size_t)(blk - 1);
+}
+
+hexa_status hexa_moe_padded_index(const hexa_moe_shape* shape, hexa_moe_idx idx, int32_t blk, int32_t* v,
+                                  size_t v_entries, int32_t* idx_pad, void* stream) {
+    MoeDims D;
+    const hexa_status s = check_shape(shape, &D);
+    if (s != HEXA_OK) return s;
+    if (blk <= 0 || (size_t)D.A + (size_t)D.E * (size_t)(blk - 1) > 0x7fffffffull) return HEXA_ERR_SHAPE;
+    if (any_null({idx.offsets, idx.perm, v, idx_pad})) return HEXA_ERR_NULL;
+    if (v_entries < hexa_moe_padded_capacity(shape, blk)) return HEXA_ERR_WORKSPACE;
+    return dev(launch_padded_index(D, idx, blk, (long long)v_entries, v, idx_pad, (hipStream_t)stream));
+}
+
 hexa_status hexa_moe_allocate(int32_t n, const double* latency, int64_t total, int64_t granule,
                               int64_t* share) {
     if (!latency || !share) return HEXA_ERR_NULL;

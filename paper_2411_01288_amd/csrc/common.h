@@ -110,6 +110,8 @@ size_t colsum_partial_rows(const MoeDims& D);   // rows of MoeWorkspace::colpart
 hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx out, void* scratch,
                         hipStream_t st);
 size_t index_scratch_bytes(const MoeDims& D);
+hipError_t launch_padded_index(const MoeDims& D, const hexa_moe_idx& idx, int blk, long long cap,
+                               int32_t* v, int32_t* idx_, hipStream_t st);
 
 template <typename T>
 hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,

@@ -158,7 +158,58 @@ __global__ __launch_bounds__(256) void index_scatter(const int32_t* __restrict__
     }
 }
 
+// The paper's padded form of the index (App. B Alg. 1; Sec. 3.2), derived from the unpadded one:
+// expert e's sub-vector starts at idx_[e] = sum over e' < e of ceil(n_e' / blk) * blk and holds its
+// perm entries followed by -1 up to the next multiple of blk; entries past idx_[E] are -1 too.
+// Two launches: the padded starts (one workgroup, E <= 1024 threads), then one thread per entry
+// of v, which finds its expert by bisection over the padded starts.
+__global__ __launch_bounds__(1024) void padded_starts(const int32_t* __restrict__ offsets, int E, int blk,
+                                                      int32_t* __restrict__ idx_) {
+    __shared__ int s[1024];
+    const int e = threadIdx.x;
+    const int n = e < E ? offsets[e + 1] - offsets[e] : 0;
+    const int padded = ceil_div(n, blk) * blk;
+    s[e] = padded;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {     // inclusive scan
+        const int v = e >= off ? s[e - off] : 0;
+        __syncthreads();
+        s[e] += v;
+        __syncthreads();
+    }
+    if (e < E) idx_[e + 1] = s[e];
+    if (e == 0) idx_[0] = 0;
+}
+
+__global__ __launch_bounds__(256) void padded_fill(const int32_t* __restrict__ offsets,
+                                                   const int32_t* __restrict__ perm,
+                                                   const int32_t* __restrict__ idx_, int E, long long cap,
+                                                   int32_t* __restrict__ v) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= cap) return;
+    int out = -1;
+    if (i < idx_[E]) {
+        int lo = 0, hi = E;                         // largest e with idx_[e] <= i
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (idx_[mid] <= i) lo = mid; else hi = mid;
+        }
+        const int r = (int)(i - idx_[lo]);
+        if (r < offsets[lo + 1] - offsets[lo]) out = perm[offsets[lo] + r];
+    }
+    v[i] = out;
+}
+
 }  // namespace
+
+hipError_t launch_padded_index(const MoeDims& D, const hexa_moe_idx& idx, int blk, long long cap,
+                               int32_t* v, int32_t* idx_, hipStream_t st) {
+    ProfScope ps(st, "padded_index");
+    hipLaunchKernelGGL(padded_starts, dim3(1), dim3(1024), 0, st, idx.offsets, D.E, blk, idx_);
+    hipLaunchKernelGGL(padded_fill, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, st, idx.offsets,
+                       idx.perm, idx_, D.E, cap, v);
+    return hipGetLastError();
+}
 
 size_t index_scratch_bytes(const MoeDims& D) {
     const IndexPlan p = plan_for(D.A);
