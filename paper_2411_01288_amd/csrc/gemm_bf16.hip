@@ -14,8 +14,8 @@
 // What is kept from the paper: rows of a tile all belong to one expert, so a tile needs one
 // expert's weights; rows are addressed through the re-index vector, so nothing is padded to a
 // capacity and nothing is dropped.  What is not: the 16x16x16 warp tiles, the per-expert serial
-// loop of Alg. 4 and the padded (-1) re-index vector.  Here a workgroup owns a 256x256 (or
-// 128-wide) tile, each 64-lane wavefront a grid of 32x32x16 bf16 MFMA blocks, operands go from
+// loop of Alg. 4 and the padded (-1) re-index vector.  Here a workgroup owns a 256x256 tile,
+// each 64-lane wavefront a grid of 32x32x16 bf16 MFMA blocks, operands go from
 // global memory straight into LDS (no registers in between) as [row][64 k] with a 16-byte XOR
 // swizzle (conflict-free 128-bit reads); operands whose contraction index is the slow one in
 // memory (weights in the forward GEMMs, both operands of the token contractions) keep their
@@ -81,18 +81,16 @@ __device__ __forceinline__ void gelu_both(float u, float& h, float& g) {
     g = (1.f - r) * t;
 }
 
-// LDS image of a K-contiguous operand: row r = BK*2 bytes = CPRK chunks of 16 bytes (8 bf16 along
-// k); chunk c of row r sits at position c ^ key(r).  gfx950's LDS serves 128-bit reads 16 lanes
+// LDS image of a K-contiguous operand: row r = BK*2 = 128 bytes = CPRK chunks of 16 bytes (8 bf16
+// along k); chunk c of row r sits at position c ^ key(r).  gfx950's LDS serves 128-bit reads 16 lanes
 // (256 bytes, 64 banks) per clock; a 32x32x16 fragment read has 16 consecutive lanes on 16
-// consecutive rows with one chunk index.  With 64-byte rows four consecutive rows fill the 256
-// bytes of bank space, so rows r, r+4, r+8, r+12 must sit on four different chunk positions:
-// key(r) = (r >> 2) & 3.  (With 128-byte rows the same argument gives (r >> 1) & 7.)
+// consecutive rows with one chunk index.  Two consecutive 128-byte rows fill the 256 bytes of bank
+// space, so rows r, r+2, ..., r+14 must sit on eight different chunk positions:
+// key(r) = (r >> 1) & 7.
 constexpr int CPRK = BK * 2 / 16;                 // chunks per row
 constexpr int ROWB = BK * 2;                      // bytes per row
-static_assert(BK == 32 || BK == 64, "stage depth");
-__device__ __forceinline__ uint32_t lds_swz(int row) {
-    return BK == 32 ? (uint32_t)((row >> 2) & 3) : (uint32_t)((row >> 1) & 7);
-}
+static_assert(BK == 64, "the K loop and the swizzle are written for 64-element blocks");
+__device__ __forceinline__ uint32_t lds_swz(int row) { return (uint32_t)((row >> 1) & 7); }
 
 // ---------------------------------------------------------------------------------------------
 // Operand staging: global -> LDS without passing through registers.
