@@ -28,7 +28,16 @@ def _cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("T,d,f,E,k,routing,seed", _cases(20, 20241127))
+EXTREMES = [
+    (300, 64, 64, 1024, 2, "topk", 501),      # the largest expert count: almost every expert empty or one row
+    (2000, 64, 128, 1024, 3, "zipf", 502),
+    (20000, 64, 64, 2, 2, "topk", 503),       # long segments, several weight-gradient chunks, tiny features
+    (257, 1024, 64, 3, 1, "topk", 504),       # d >> f
+    (257, 64, 1536, 3, 1, "topk", 505),       # f >> d
+]
+
+
+@pytest.mark.parametrize("T,d,f,E,k,routing,seed", _cases(20, 20241127) + EXTREMES)
 def test_random_bf16_shape(oracle, T, d, f, E, k, routing, seed):
     w = MoEWorkload("rnd", T, d, f, E, k, "bf16", routing, seed)
     data = generate(w, DEV)
