@@ -47,6 +47,12 @@ namespace {
 const double kC = 0.79788456080286535588;  // sqrt(2/pi)
 const double kA = 0.044715;
 
+// The activation F of the layer (Table 5 rows 2 and 7; the paper does not name it).  Kind 0, the
+// default and the reading used for every workload, is GELU in its tanh form; ReLU (1) and SiLU (2)
+// are the other two the library offers.  The kind is a process-wide setting of this test oracle
+// (hexa_oracle_set_activation), read by every forward / backward routine.
+int g_act = 0;
+
 inline double gelu(double u) {
     return 0.5 * u * (1.0 + std::tanh(kC * (u + kA * u * u * u)));
 }
@@ -55,6 +61,21 @@ inline double gelu_grad(double u) {
     const double s = kC * (u + kA * u * u * u);
     const double th = std::tanh(s);
     return 0.5 * (1.0 + th) + 0.5 * u * (1.0 - th * th) * kC * (1.0 + 3.0 * kA * u * u);
+}
+
+inline double act(double u) {
+    if (g_act == 1) return u > 0.0 ? u : 0.0;              // ReLU
+    if (g_act == 2) return u / (1.0 + std::exp(-u));       // SiLU: u * sigmoid(u)
+    return gelu(u);
+}
+
+inline double act_grad(double u) {
+    if (g_act == 1) return u > 0.0 ? 1.0 : 0.0;            // derivative taken as 0 at u = 0
+    if (g_act == 2) {
+        const double sg = 1.0 / (1.0 + std::exp(-u));
+        return sg * (1.0 + u * (1.0 - sg));
+    }
+    return gelu_grad(u);
 }
 
 struct Dims { int T, d, f, E, k; };
@@ -136,7 +157,7 @@ int hexa_oracle_fwd(int T, int d, int f, int E, int k, const float* x, const int
                 const int e = topk_idx[(size_t)t * k + j];
                 const double g = (double)gate[(size_t)t * k + j];
                 first_mlp(D, x + (size_t)t * d, W1 + (size_t)e * d * f, b1 + (size_t)e * f, pre);
-                for (int q = 0; q < f; ++q) h[q] = gelu(pre[q]);                 // row 2
+                for (int q = 0; q < f; ++q) h[q] = act(pre[q]);                  // row 2
                 second_mlp(D, h, W2 + (size_t)e * f * d, b2 + (size_t)e * d, o);
                 for (int m = 0; m < d; ++m) y[m] += g * o[m];                    // sum over the k slots
             }
@@ -169,7 +190,7 @@ int hexa_oracle_bwd_tokens(int T, int d, int f, int E, int k, const float* x,
                 const float* W1e = W1 + (size_t)e * d * f;
                 const float* W2e = W2 + (size_t)e * f * d;
                 first_mlp(D, x + (size_t)t * d, W1e, b1 + (size_t)e * f, pre);
-                for (int q = 0; q < f; ++q) h[q] = gelu(pre[q]);
+                for (int q = 0; q < f; ++q) h[q] = act(pre[q]);
                 second_mlp(D, h, W2e, b2 + (size_t)e * d, o);
                 double dg = 0.0;
                 for (int m = 0; m < d; ++m) {
@@ -182,7 +203,7 @@ int hexa_oracle_bwd_tokens(int T, int d, int f, int E, int k, const float* x,
                     const float* w = W2e + (size_t)q * d;
                     double dh = 0.0;
                     for (int m = 0; m < d; ++m) dh += dob[m] * (double)w[m];
-                    dpre[q] = dh * gelu_grad(pre[q]);
+                    dpre[q] = dh * act_grad(pre[q]);
                 }
                 for (int i = 0; i < d; ++i) {                          // row 10
                     const float* w = W1e + (size_t)i * f;
@@ -251,14 +272,14 @@ int hexa_oracle_bwd_experts(int T, int d, int f, int E, int k, const float* x,
             }
             for (int c = 0; c < nc; ++c) {
                 const int n = cols ? cols[c] : c;
-                const double hn = gelu(pre[c]);
+                const double hn = act(pre[c]);
                 const float* w = W2e + (size_t)n * d;
                 double dh = 0.0;
                 for (int m = 0; m < d; ++m) {
                     dW2[(size_t)c * d + m] += hn * dob[m];
                     dh += dob[m] * (double)w[m];
                 }
-                dpre[c] = dh * gelu_grad(pre[c]);
+                dpre[c] = dh * act_grad(pre[c]);
                 db1[c] += dpre[c];
             }
             for (int i = 0; i < d; ++i) {
@@ -343,5 +364,13 @@ int hexa_oracle_route(int T, int E, int k, int mode, const float* logits, int32_
 // pinned on their own.
 double hexa_oracle_gelu(double u) { return gelu(u); }
 double hexa_oracle_gelu_grad(double u) { return gelu_grad(u); }
+// Selects the activation (0 GELU-tanh, 1 ReLU, 2 SiLU) for all later calls; returns 1 on a bad kind.
+int hexa_oracle_set_activation(int kind) {
+    if (kind < 0 || kind > 2) return 1;
+    g_act = kind;
+    return 0;
+}
+double hexa_oracle_act(double u) { return act(u); }
+double hexa_oracle_act_grad(double u) { return act_grad(u); }
 
 }  // extern "C"

@@ -40,6 +40,10 @@ def lib():
         _lib.hexa_oracle_gelu.argtypes = [ctypes.c_double]
         _lib.hexa_oracle_gelu_grad.restype = ctypes.c_double
         _lib.hexa_oracle_gelu_grad.argtypes = [ctypes.c_double]
+        _lib.hexa_oracle_act.restype = ctypes.c_double
+        _lib.hexa_oracle_act.argtypes = [ctypes.c_double]
+        _lib.hexa_oracle_act_grad.restype = ctypes.c_double
+        _lib.hexa_oracle_act_grad.argtypes = [ctypes.c_double]
     return _lib
 
 
@@ -175,3 +179,20 @@ def gelu(u: float) -> float:
 
 def gelu_grad(u: float) -> float:
     return lib().hexa_oracle_gelu_grad(float(u))
+
+
+ACT_GELU_TANH, ACT_RELU, ACT_SILU = 0, 1, 2
+
+
+def set_activation(kind: int) -> None:
+    """Process-wide activation of the oracle (0 GELU-tanh, the default; 1 ReLU; 2 SiLU)."""
+    if lib().hexa_oracle_set_activation(int(kind)):
+        raise ValueError("oracle: unknown activation")
+
+
+def act(u: float) -> float:
+    return lib().hexa_oracle_act(float(u))
+
+
+def act_grad(u: float) -> float:
+    return lib().hexa_oracle_act_grad(float(u))

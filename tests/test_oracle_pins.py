@@ -64,8 +64,9 @@ def dense_masked_forward(c):
     return np.einsum("te,tem->tm", m, o), m, pre, h, o
 
 
-def torch_loop_grads(c):
+def torch_loop_grads(c, act=None):
     """Library cross-check: autograd through a per-expert python loop, fp64."""
+    act = act or (lambda z: torch.nn.functional.gelu(z, approximate="tanh"))
     t = {k: torch.tensor(v, dtype=torch.float64, requires_grad=(k != "dY"))
          for k, v in c.items() if k != "topk_idx"}
     idx = torch.tensor(c["topk_idx"], dtype=torch.long)
@@ -76,7 +77,7 @@ def torch_loop_grads(c):
             rows = (idx[:, j] == e).nonzero().flatten()
             if rows.numel() == 0:
                 continue
-            h = torch.nn.functional.gelu(t["x"][rows] @ t["W1"][e] + t["b1"][e], approximate="tanh")
+            h = act(t["x"][rows] @ t["W1"][e] + t["b1"][e])
             y = y.index_add(0, rows, t["gate"][rows, j, None] * (h @ t["W2"][e] + t["b2"][e]))
     (y * t["dY"]).sum().backward()
     g = lambda n: (t[n].grad if t[n].grad is not None else torch.zeros_like(t[n])).numpy()
@@ -412,3 +413,41 @@ def test_padded_index_against_brute_force(oracle, T, k, E, blk):
     assert v[v >= 0].tolist() == perm.tolist()
     with pytest.raises(ValueError):
         oracle.padded_index(idx, E, blk, cap=exp_s[-1] - 1)
+
+
+# ---------------------------------------------------- the other activations (ReLU, SiLU)
+@pytest.fixture
+def with_activation(oracle):
+    """Sets the oracle's process-wide activation for one test and restores GELU-tanh."""
+    def choose(kind):
+        oracle.set_activation(kind)
+    yield choose
+    oracle.set_activation(0)
+
+
+@pytest.mark.parametrize("kind,lib_act", [(1, torch.nn.functional.relu), (2, torch.nn.functional.silu)])
+def test_other_activations_match_autograd_loop(oracle, with_activation, kind, lib_act):
+    with_activation(kind)
+    c = small_case(40 + kind, T=60, d=8, f=24, E=5, k=2, dup=True)
+    c["topk_idx"][c["topk_idx"] == 3] = 0
+    y, g = oracle_all(oracle, c)
+    yt, gt = torch_loop_grads(c, act=lib_act)
+    assert rel(y, yt) < 1e-13
+    for n in g:
+        assert rel(g[n], gt[n]) < 1e-12, n
+
+
+def test_activation_scalar_values(oracle, with_activation):
+    with_activation(1)
+    assert [oracle.act(u) for u in (-2.0, 0.0, 3.5)] == [0.0, 0.0, 3.5]
+    assert [oracle.act_grad(u) for u in (-2.0, 0.0, 3.5)] == [0.0, 0.0, 1.0]
+    with_activation(2)
+    for u in (-4.0, -0.3, 0.0, 0.7, 5.0):
+        assert abs(oracle.act(u) - u / (1 + np.exp(-u))) < 1e-15
+        e = 1e-6
+        assert abs((oracle.act(u + e) - oracle.act(u - e)) / (2 * e) - oracle.act_grad(u)) < 1e-9
+    assert oracle.act_grad(0.0) == 0.5
+    with_activation(0)
+    assert oracle.act(0.9) == oracle.gelu(0.9) and oracle.act_grad(0.9) == oracle.gelu_grad(0.9)
+    with pytest.raises(ValueError):
+        oracle.set_activation(7)
