@@ -48,16 +48,22 @@ typedef enum {
     HEXA_OK = 0,
     HEXA_ERR_NULL = 1,        /* a required pointer is NULL */
     HEXA_ERR_SHAPE = 2,       /* a size is <= 0, A overflows int32, or E > 1024 */
-    HEXA_ERR_UNSUPPORTED = 3, /* dtype unknown, or a bf16 size rule (see above) is not met */
+    HEXA_ERR_UNSUPPORTED = 3, /* dtype or activation unknown, or a bf16 size rule (see above) is not met */
     HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query */
     HEXA_ERR_DEVICE = 5       /* a launch failed (hipGetLastError) */
 } hexa_status;
 
 typedef enum { HEXA_F32 = 0, HEXA_BF16 = 1 } hexa_dtype;
 
+/* The activation F between the two linear layers (App. B Table 5 rows 2 and 7).  The paper does not
+ * name it; 0, GELU in its tanh form (constants sqrt(2/pi), 0.044715), is the reading used for every
+ * benchmark workload.  ReLU takes derivative 0 at 0. */
+typedef enum { HEXA_ACT_GELU_TANH = 0, HEXA_ACT_RELU = 1, HEXA_ACT_SILU = 2 } hexa_activation;
+
 typedef struct {
     int32_t T, d_model, d_ff, E, k;
-    int32_t dtype; /* hexa_dtype */
+    int32_t dtype;      /* hexa_dtype */
+    int32_t activation; /* hexa_activation */
 } hexa_moe_shape;
 
 /* The re-index structures (Sec. 3.2; App. B Alg. 1 and Table 4), all dev:
@@ -109,7 +115,7 @@ HEXA_API hexa_status hexa_moe_padded_index(const hexa_moe_shape *shape, hexa_moe
                                   int32_t *v, size_t v_entries, int32_t *idx_pad, void *stream);
 
 /* Forward (App. B Table 5 rows 1-3; ESMM of Sec. 3.1):
- *   pre_a = x_t W1[e_a] + b1[e_a];  h_a = GELU_tanh(pre_a);  o_a = h_a W2[e_a] + b2[e_a]
+ *   pre_a = x_t W1[e_a] + b1[e_a];  h_a = F(pre_a);  o_a = h_a W2[e_a] + b2[e_a]
  *   y_t   = sum_j gate[t,j] * o_{t*k+j}
  * (the paper's table sums the k slots unweighted; the gate factor is this
  * library's reading, equal to the paper's for gate == 1).
@@ -119,7 +125,7 @@ HEXA_API hexa_status hexa_moe_padded_index(const hexa_moe_shape *shape, hexa_moe
  *   y [T,d]    dev, out, shape.dtype
  *   workspace  dev, >= hexa_moe_workspace_bytes(); afterwards holds the saved
  *              state hexa_moe_bwd reads
- * bf16: products in bf16 MFMA with fp32 accumulation; h, GELU'(pre) and the per-assignment
+ * bf16: products in bf16 MFMA with fp32 accumulation; h, F'(pre) and the per-assignment
  * outputs o are stored rounded to bf16 (round-to-nearest-even), the k-slot sum runs
  * in fp32. */
 HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, const int32_t *topk_idx,
@@ -130,7 +136,7 @@ HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, co
 /* Backward (App. B Table 5 rows 4-10; ESS and ESTMM of Sec. 3.1), with
  * do_a = gate_a * dY_t:
  *   db2[e] = sum_{a in e} do_a            dW2[e] = sum_{a in e} h_a^T do_a
- *   dh_a = do_a W2[e_a]^T                 dpre_a = dh_a * GELU_tanh'(pre_a)
+ *   dh_a = do_a W2[e_a]^T                 dpre_a = dh_a * F'(pre_a)
  *   db1[e] = sum_{a in e} dpre_a          dW1[e] = sum_{a in e} x_t^T dpre_a
  *   dx_t = sum_j dpre_{t*k+j} W1[e]^T     dgate[t,j] = <dY_t, o_{t*k+j}>
  *   dY [T,d]                                    dev, in, shape.dtype

@@ -25,7 +25,8 @@ EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe
 
 class Shape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
-                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("activation", ctypes.c_int32)]
 
 
 class Idx(ctypes.Structure):
@@ -83,12 +84,15 @@ def _check(code: int):
         raise HexaError(code)
 
 
-def make_shape(T: int, d_model: int, d_ff: int, E: int, k: int, dtype) -> Shape:
+ACT_GELU_TANH, ACT_RELU, ACT_SILU = 0, 1, 2
+
+
+def make_shape(T: int, d_model: int, d_ff: int, E: int, k: int, dtype, activation: int = ACT_GELU_TANH) -> Shape:
     if isinstance(dtype, torch.dtype):
         dtype = {torch.float32: HEXA_F32, torch.bfloat16: HEXA_BF16}[dtype]
     elif isinstance(dtype, str):
         dtype = {"f32": HEXA_F32, "bf16": HEXA_BF16}[dtype]
-    return Shape(T, d_model, d_ff, E, k, dtype)
+    return Shape(T, d_model, d_ff, E, k, dtype, int(activation))
 
 
 def _tdt(shape: Shape):

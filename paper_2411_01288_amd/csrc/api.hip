@@ -36,6 +36,7 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (s->E > kMaxExperts) return HEXA_ERR_SHAPE;
     if ((long long)s->T * s->k > 0x7fffffffLL) return HEXA_ERR_SHAPE;
     if (s->dtype != HEXA_F32 && s->dtype != HEXA_BF16) return HEXA_ERR_UNSUPPORTED;
+    if (s->activation < HEXA_ACT_GELU_TANH || s->activation > HEXA_ACT_SILU) return HEXA_ERR_UNSUPPORTED;
     if (s->dtype == HEXA_BF16) {
         if (s->d_model % 64 != 0 || s->d_ff % 64 != 0) return HEXA_ERR_UNSUPPORTED;
         // the bf16 kernels address x (gathered rows) and one expert's weight matrix with 32-bit
@@ -45,6 +46,7 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
             return HEXA_ERR_UNSUPPORTED;
     }
     D->T = s->T; D->d = s->d_model; D->f = s->d_ff; D->E = s->E; D->k = s->k; D->A = s->T * s->k;
+    D->act = s->activation;
     return HEXA_OK;
 }
 

@@ -81,7 +81,7 @@ struct ProfScope {
 };
 
 // ---- internal launchers (one per translation unit), all asynchronous on `st` ----
-struct MoeDims { int T, d, f, E, k, A; };
+struct MoeDims { int T, d, f, E, k, A, act; };
 
 // saved + staging regions inside the caller's workspace (device pointers)
 struct MoeWorkspace {

@@ -23,6 +23,7 @@ struct RowsArgs {
     float* out0;           // [A][N]
     float* out1;           // FC1: h
     int K, N, E, mode;
+    int act;               // hexa_activation (FC1, DGRAD2)
     const int32_t* offsets;
 };
 
@@ -33,6 +34,21 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
     const float th = tanhf(HEXA_GELU_C * (u + HEXA_GELU_A * u * u * u));
     return 0.5f * (1.f + th) +
            0.5f * u * (1.f - th * th) * HEXA_GELU_C * (1.f + 3.f * HEXA_GELU_A * u * u);
+}
+
+// F and F' for the three activations (accurate library functions: this is the 1e-5 path)
+__device__ __forceinline__ float act_f(float u, int act) {
+    if (act == HEXA_ACT_RELU) return u > 0.f ? u : 0.f;
+    if (act == HEXA_ACT_SILU) return u / (1.f + expf(-u));
+    return gelu_f(u);
+}
+__device__ __forceinline__ float act_grad_f(float u, int act) {
+    if (act == HEXA_ACT_RELU) return u > 0.f ? 1.f : 0.f;
+    if (act == HEXA_ACT_SILU) {
+        const float sg = 1.f / (1.f + expf(-u));
+        return sg * (1.f + u * (1.f - sg));
+    }
+    return gelu_grad_f(u);
 }
 
 // ESMM (Sec. 3.1 item 1; App. B Alg. 2): one 16x16 output tile of one expert segment per workgroup.
@@ -66,9 +82,9 @@ __global__ __launch_bounds__(256) void f32_rows_gemm(RowsArgs a) {
     if (a.bias) acc += a.bias[(size_t)s.e * a.N + n];
     if (a.mode == F32_FC1) {
         a.out0[oi] = acc;
-        a.out1[oi] = gelu_f(acc);
+        a.out1[oi] = act_f(acc, a.act);
     } else if (a.mode == F32_DGRAD2) {
-        a.out0[oi] = acc * gelu_grad_f(a.pre_in[oi]);
+        a.out0[oi] = acc * act_grad_f(a.pre_in[oi], a.act);
     } else {
         a.out0[oi] = acc;
     }
@@ -124,8 +140,8 @@ hipError_t launch_f32_fwd(const MoeDims& D, const float* x, const float* W1, con
                           const float* W2, const float* b2, const hexa_moe_idx& idx,
                           const MoeWorkspace& ws, hipStream_t st) {
     RowsArgs a{};
-    a.offsets = idx.offsets; a.perm = idx.perm; a.k = D.k; a.E = D.E;
-    // fc1: pre = x W1 + b1, h = GELU(pre)
+    a.offsets = idx.offsets; a.perm = idx.perm; a.k = D.k; a.E = D.E; a.act = D.act;
+    // fc1: pre = x W1 + b1, h = F(pre)
     a.A = x; a.lda = D.d; a.gather = 1;
     a.B = W1; a.b_expert_stride = (size_t)D.d * D.f; a.sbk = D.f; a.sbn = 1;
     a.bias = b1; a.out0 = (float*)ws.pre; a.out1 = (float*)ws.h; a.K = D.d; a.N = D.f; a.mode = F32_FC1;
@@ -142,7 +158,7 @@ hipError_t launch_f32_bwd(const MoeDims& D, const float* x, const float* W1, con
                           const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
                           hipStream_t st) {
     RowsArgs a{};
-    a.offsets = idx.offsets; a.perm = idx.perm; a.k = D.k; a.E = D.E; a.gather = 0;
+    a.offsets = idx.offsets; a.perm = idx.perm; a.k = D.k; a.E = D.E; a.act = D.act; a.gather = 0;
     // dh = do W2^T ; dpre = dh * GELU'(pre)
     a.A = (const float*)ws.dout; a.lda = D.d;
     a.B = W2; a.b_expert_stride = (size_t)D.f * D.d; a.sbk = 1; a.sbn = D.d;

@@ -3,7 +3,7 @@
 // Six contractions share one tile routine (forward: one grid each; backward: the input-gradient
 // and weight-gradient contractions of a linear layer share a grid):
 //   row GEMMs  (ESMM, App. B Alg. 2): rows are one expert segment of the re-index vector
-//       FC1     pre = x[perm/k] W1[e] + b1[e],  h = GELU(pre), g = GELU'(pre) saved   K = d, N = f
+//       FC1     pre = x[perm/k] W1[e] + b1[e],  h = F(pre), g = F'(pre) saved        K = d, N = f
 //       FC2     o   = h W2[e] + b2[e]   (stored as bf16)                 K = f, N = d
 //       DGRAD2  dpre = (do W2[e]^T) * g                              K = d, N = f
 //       DGRAD1  dxp = dpre W1[e]^T      (stored as bf16)                 K = f, N = d
@@ -79,6 +79,22 @@ __device__ __forceinline__ void gelu_both(float u, float& h, float& g) {
     h = u - ur;
     const float t = 1.f + ur * (2.f * HEXA_GELU_C + 6.f * HEXA_GELU_C * HEXA_GELU_A * (u * u));
     g = (1.f - r) * t;
+}
+
+// The same pair for the other activations: ReLU (derivative 0 at 0) and SiLU u s(u), s = 1/(1+e^-u),
+// with derivative s (1 + u (1 - s)).
+template <int ACT>
+__device__ __forceinline__ void act_both(float u, float& h, float& g) {
+    if constexpr (ACT == HEXA_ACT_RELU) {
+        h = u > 0.f ? u : 0.f;
+        g = u > 0.f ? 1.f : 0.f;
+    } else if constexpr (ACT == HEXA_ACT_SILU) {
+        const float sg = fast_rcp(1.f + fast_exp2(-1.4426950408889634f * u));
+        h = u * sg;
+        g = sg * (1.f + u * (1.f - sg));
+    } else {
+        gelu_both(u, h, g);
+    }
 }
 
 // LDS image of a K-contiguous operand: row r = BK*2 = 128 bytes = CPRK chunks of 16 bytes (8 bf16
@@ -267,7 +283,7 @@ __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restric
 // The kernel
 // ---------------------------------------------------------------------------------------------
 // One work-item slot `item` (slot i is dispatched to XCD i % 8) of contraction OP.
-template <int BM, int BN, int WM, int WN, int OP>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -651,7 +667,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         if constexpr (OP == OP_FC1) {
                             float hh[4], gg[4];
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) gelu_both(v[r], hh[r], gg[r]);
+                            for (int r = 0; r < 4; ++r) act_both<ACT>(v[r], hh[r], gg[r]);
                             u32x2 pz, hz;
                             pz.x = pack_bf2(gg[0], gg[1]); pz.y = pack_bf2(gg[2], gg[3]);
                             hz.x = pack_bf2(hh[0], hh[1]); hz.y = pack_bf2(hh[2], hh[3]);
@@ -718,9 +734,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #undef STORE16
 }
 
-template <int BM, int BN, int WM, int WN, int OP>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
-    gemm_tile<BM, BN, WM, WN, OP>(g, (int)blockIdx.x);
+    gemm_tile<BM, BN, WM, WN, OP, ACT>(g, (int)blockIdx.x);
 }
 
 // Two independent contractions in one grid (the paper's fused backward kernel, Sec. 3.2 "Fused
@@ -763,10 +779,10 @@ __global__ __launch_bounds__(256) void wgrad_finish(const int32_t* __restrict__ 
 
 constexpr int kNumCUs = 256;
 
-template <int BM, int BN, int WM, int WN, int OP>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
 void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label) {
     ProfScope ps(st, label);
-    auto kern = gemm_bf16<BM, BN, WM, WN, OP>;
+    auto kern = gemm_bf16<BM, BN, WM, WN, OP, ACT>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
@@ -854,7 +870,9 @@ hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
     launch_worklists(D, idx, ws, st);
     g.A = x; g.a_rows = D.T; g.B = W1; g.bias = b1; g.out0 = ws.pre; g.out1 = ws.h; g.K = D.d; g.N = D.f;
-    launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st, "fc1");
+    if (D.act == HEXA_ACT_RELU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_RELU>(D, g, st, "fc1");
+    else if (D.act == HEXA_ACT_SILU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_SILU>(D, g, st, "fc1");
+    else launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st, "fc1");
     g.A = (const bf16_t*)ws.h; g.B = W2; g.bias = b2; g.out0 = ws.o; g.out1 = nullptr; g.K = D.f; g.N = D.d;
     launch_rows<TBM, TBN, TWM, TWN, OP_FC2>(D, g, st, "fc2");
     return hipGetLastError();

@@ -42,7 +42,8 @@ def test_size_queries_and_shape_validation(B):
                 B.make_shape(8, 64, 64, 2000, 1, "bf16"),          # E > 1024
                 B.make_shape(2 ** 30, 64, 64, 4, 4, "bf16"),       # T*k overflows int32
                 B.make_shape(8, 60, 64, 4, 1, "bf16"),             # bf16 needs multiples of 64
-                B.Shape(8, 64, 64, 4, 1, 7)):                      # unknown dtype
+                B.Shape(8, 64, 64, 4, 1, 7, 0),                    # unknown dtype
+                B.make_shape(8, 64, 64, 4, 1, "bf16", 3)):         # unknown activation
         assert B.workspace_bytes(bad) == 0 and B.index_scratch_bytes(bad) == 0
 
 
