@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--routing", default=None, help="override the routing recipe (zipf, forced, ...)")
+    ap.add_argument("--dtype", default=None, help="override the element type (bf16, f16, f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of the step captured into one HIP graph (launch-latency regime: "
@@ -111,6 +112,8 @@ def main():
     from paper_2411_01288_amd.workloads import generate, workload
 
     ov = {"routing": args.routing} if args.routing else {}
+    if args.dtype:
+        ov["dtype"] = args.dtype
     w = workload(args.workload, **ov)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -16,13 +16,13 @@
  *     synchronises; all work is enqueued on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and the call returns at once.
  *   - All tensors are dense, row-major, without strides.
- *   - Element type `shape.dtype` (HEXA_F32 or HEXA_BF16) applies to x, W1, b1,
+ *   - Element type `shape.dtype` (HEXA_F32, HEXA_BF16 or HEXA_F16) applies to x, W1, b1,
  *     W2, b2, y, dY, dx.  gate and dgate are float.  Weight and bias gradients
  *     are float (the accumulation type).  Index tensors are int32.
  *   - Outputs are overwritten, never accumulated into.
  *   - Errors are return codes; argument checks run on the host before any
  *     launch, so a non-OK return means nothing was enqueued.
- *   - HEXA_BF16 needs d % 64 == 0 and f % 64 == 0 (the paper's kernels likewise
+ *   - HEXA_BF16 and HEXA_F16 (the MFMA paths) need d % 64 == 0 and f % 64 == 0 (the paper's kernels likewise
  *     assume feature sizes divisible by the tile, App. B), T*d*2 < 2^32 and
  *     d*f*2 < 2^32 (32-bit byte offsets inside x and inside one expert's weight
  *     matrix); HEXA_F32 takes any positive sizes.  E <= 1024.
@@ -53,7 +53,7 @@ typedef enum {
     HEXA_ERR_DEVICE = 5       /* a launch failed (hipGetLastError) */
 } hexa_status;
 
-typedef enum { HEXA_F32 = 0, HEXA_BF16 = 1 } hexa_dtype;
+typedef enum { HEXA_F32 = 0, HEXA_BF16 = 1, HEXA_F16 = 2 } hexa_dtype;
 
 /* The activation F between the two linear layers (App. B Table 5 rows 2 and 7).  The paper does not
  * name it; 0, GELU in its tanh form (constants sqrt(2/pi), 0.044715), is the reading used for every
@@ -125,8 +125,8 @@ HEXA_API hexa_status hexa_moe_padded_index(const hexa_moe_shape *shape, hexa_moe
  *   y [T,d]    dev, out, shape.dtype
  *   workspace  dev, >= hexa_moe_workspace_bytes(); afterwards holds the saved
  *              state hexa_moe_bwd reads
- * bf16: products in bf16 MFMA with fp32 accumulation; h, F'(pre) and the per-assignment
- * outputs o are stored rounded to bf16 (round-to-nearest-even), the k-slot sum runs
+ * bf16 / fp16: products in MFMA of that type with fp32 accumulation; h, F'(pre) and the
+ * per-assignment outputs o are stored rounded to the element type (round-to-nearest-even), the k-slot sum runs
  * in fp32. */
 HEXA_API hexa_status hexa_moe_fwd(const hexa_moe_shape *shape, const void *x, const int32_t *topk_idx,
                          const float *gate, const void *W1, const void *b1, const void *W2,

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 
-HEXA_F32, HEXA_BF16 = 0, 1
+HEXA_F32, HEXA_BF16, HEXA_F16 = 0, 1, 2
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
            "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
            "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route",
@@ -89,14 +89,14 @@ ACT_GELU_TANH, ACT_RELU, ACT_SILU = 0, 1, 2
 
 def make_shape(T: int, d_model: int, d_ff: int, E: int, k: int, dtype, activation: int = ACT_GELU_TANH) -> Shape:
     if isinstance(dtype, torch.dtype):
-        dtype = {torch.float32: HEXA_F32, torch.bfloat16: HEXA_BF16}[dtype]
+        dtype = {torch.float32: HEXA_F32, torch.bfloat16: HEXA_BF16, torch.float16: HEXA_F16}[dtype]
     elif isinstance(dtype, str):
-        dtype = {"f32": HEXA_F32, "bf16": HEXA_BF16}[dtype]
+        dtype = {"f32": HEXA_F32, "bf16": HEXA_BF16, "f16": HEXA_F16}[dtype]
     return Shape(T, d_model, d_ff, E, k, dtype, int(activation))
 
 
 def _tdt(shape: Shape):
-    return torch.float32 if shape.dtype == HEXA_F32 else torch.bfloat16
+    return {HEXA_F32: torch.float32, HEXA_BF16: torch.bfloat16, HEXA_F16: torch.float16}[shape.dtype]
 
 
 def _ptr(t: Optional[torch.Tensor], dims, dtype, name: str):

@@ -35,9 +35,9 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (s->T <= 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return HEXA_ERR_SHAPE;
     if (s->E > kMaxExperts) return HEXA_ERR_SHAPE;
     if ((long long)s->T * s->k > 0x7fffffffLL) return HEXA_ERR_SHAPE;
-    if (s->dtype != HEXA_F32 && s->dtype != HEXA_BF16) return HEXA_ERR_UNSUPPORTED;
+    if (s->dtype != HEXA_F32 && s->dtype != HEXA_BF16 && s->dtype != HEXA_F16) return HEXA_ERR_UNSUPPORTED;
     if (s->activation < HEXA_ACT_GELU_TANH || s->activation > HEXA_ACT_SILU) return HEXA_ERR_UNSUPPORTED;
-    if (s->dtype == HEXA_BF16) {
+    if (s->dtype != HEXA_F32) {
         if (s->d_model % 64 != 0 || s->d_ff % 64 != 0) return HEXA_ERR_UNSUPPORTED;
         // the bf16 kernels address x (gathered rows) and one expert's weight matrix with 32-bit
         // byte offsets
@@ -53,7 +53,7 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
 // Carve the workspace.  base may be NULL (size query).
 MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
     MoeWorkspace w{};
-    const size_t es = dtype == HEXA_BF16 ? 2 : 4;
+    const size_t es = dtype == HEXA_F32 ? 4 : 2;
     const size_t A = (size_t)D.A, d = (size_t)D.d, f = (size_t)D.f;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -73,7 +73,7 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
         if (rows < rows_gemm) rows = rows_gemm;
         w.colpart = (float*)take(rows * (d > f ? d : f) * 4);
     }
-    if (dtype == HEXA_BF16) {
+    if (dtype != HEXA_F32) {
         w.xg = take(A * d * es);
         w.kpart_slots = wgrad_max_slots(D);
         w.kpart = (float*)take(w.kpart_slots * d * f * 4);
@@ -227,9 +227,13 @@ hexa_status hexa_moe_fwd(const hexa_moe_shape* shape, const void* x, const int32
                            (const float*)b2, idx, ws, st);
         if (e == hipSuccess) e = launch_combine_y<float>(D, (const float*)ws.o, idx.inv, gate, (float*)y, st);
     } else {
+        const bool f16 = shape->dtype == HEXA_F16;
         e = launch_bf16_fwd(D, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)b1,
-                            (const bf16_t*)W2, (const bf16_t*)b2, idx, ws, st);
-        if (e == hipSuccess) e = launch_combine_y<bf16_t>(D, (const bf16_t*)ws.o, idx.inv, gate, (bf16_t*)y, st);
+                            (const bf16_t*)W2, (const bf16_t*)b2, idx, ws, st, f16);
+        if (e == hipSuccess) {
+            if (f16) e = launch_combine_y<f16_t>(D, (const f16_t*)ws.o, idx.inv, gate, (f16_t*)y, st);
+            else e = launch_combine_y<bf16_t>(D, (const bf16_t*)ws.o, idx.inv, gate, (bf16_t*)y, st);
+        }
     }
     return dev(e);
 }
@@ -257,14 +261,22 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
             e = launch_segment_colsum<float>(D, (const float*)ws.dpre, D.f, idx.offsets, ws.colpart, db1, st);
         if (e == hipSuccess) e = launch_combine_dx<float>(D, (const float*)ws.dxp, idx.inv, (float*)dx, st);
     } else {
-        e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, (const bf16_t*)ws.o,
-                                        idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, ws.colpart, db2, st);
+        const bool f16 = shape->dtype == HEXA_F16;
+        if (f16)
+            e = launch_bwd_prologue<f16_t>(D, (const f16_t*)dY, (const f16_t*)x, (f16_t*)ws.xg, (const f16_t*)ws.o,
+                                           idx.perm, idx.offsets, gate, (f16_t*)ws.dout, dgate, ws.colpart, db2, st);
+        else
+            e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, (const bf16_t*)ws.o,
+                                            idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, ws.colpart, db2, st);
         if (e == hipSuccess)
             e = launch_bf16_bwd(D, (const bf16_t*)ws.xg, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
-                                dW1, dW2, st);
+                                dW1, dW2, st, f16);
         if (e == hipSuccess)
             e = launch_tile_colsum_finish(D, ws.colpart, D.f, idx.offsets, db1, st);
-        if (e == hipSuccess) e = launch_combine_dx<bf16_t>(D, (const bf16_t*)ws.dxp, idx.inv, (bf16_t*)dx, st);
+        if (e == hipSuccess) {
+            if (f16) e = launch_combine_dx<f16_t>(D, (const f16_t*)ws.dxp, idx.inv, (f16_t*)dx, st);
+            else e = launch_combine_dx<bf16_t>(D, (const bf16_t*)ws.dxp, idx.inv, (bf16_t*)dx, st);
+        }
     }
     return dev(e);
 }

@@ -1,5 +1,5 @@
 // Shared device helpers and the internal launcher interface of libhexa_moe.
-// gfx950 (CDNA4) only: 64-wide wavefronts, bf16 MFMA, 160 KB LDS per CU.
+// gfx950 (CDNA4) only: 64-wide wavefronts, bf16 / fp16 MFMA, 160 KB LDS per CU.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -22,6 +22,32 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+typedef _Float16 f16_t;   // IEEE binary16
+
+// two floats -> two fp16 (round to nearest even) in one word
+__device__ __forceinline__ uint32_t pack_h2(float lo, float hi) {
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
+// one word of two 16-bit values -> two floats
+template <bool F16>
+__device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+    if constexpr (F16) {
+        typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+        const f16x2_t h = __builtin_bit_cast(f16x2_t, w);
+        lo = (float)h[0]; hi = (float)h[1];
+    } else {
+        lo = __uint_as_float(w << 16); hi = __uint_as_float(w & 0xffff0000u);
+    }
+}
+template <bool F16>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    if constexpr (F16) return pack_h2(lo, hi);
+    else return pack_bf2(lo, hi);
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     __device__ static float ld(const float* p) { return *p; }
@@ -30,6 +56,10 @@ template <> struct Elem<float> {
 template <> struct Elem<bf16_t> {
     __device__ static float ld(const bf16_t* p) { return bf2f(*p); }
     __device__ static void st(bf16_t* p, float v) { *p = f2bf(v); }
+};
+template <> struct Elem<f16_t> {
+    __device__ static float ld(const f16_t* p) { return (float)*p; }
+    __device__ static void st(f16_t* p, float v) { *p = (f16_t)v; }
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -143,10 +173,10 @@ hipError_t launch_f32_bwd(const MoeDims& D, const float* x, const float* W1, con
                           const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
                           hipStream_t st);
 
-// bf16 MFMA path
+// 16-bit MFMA path: pointers are raw 16-bit storage, bf16 or (f16 = true) IEEE fp16
 hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* b1,
                            const bf16_t* W2, const bf16_t* b2, const hexa_moe_idx& idx,
-                           const MoeWorkspace& ws, hipStream_t st);
+                           const MoeWorkspace& ws, hipStream_t st, bool f16);
 hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* W2,
                            const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
-                           hipStream_t st);
+                           hipStream_t st, bool f16);

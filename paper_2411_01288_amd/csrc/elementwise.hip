@@ -40,6 +40,22 @@ template <> struct Vec<bf16_t> {
     }
 };
 
+template <> struct Vec<f16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const f16_t* p, float (&v)[8]) {
+        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) unpack2<true>(w[i], v[2 * i], v[2 * i + 1]);
+    }
+    __device__ static void store(f16_t* p, const float (&v)[8]) {
+        uint4 q;
+        q.x = pack_h2(v[0], v[1]); q.y = pack_h2(v[2], v[3]);
+        q.z = pack_h2(v[4], v[5]); q.w = pack_h2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = q;
+    }
+};
+
 // One thread per VN consecutive columns of one token.  d % VN == 0.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_rows(int T_, int d, int k,
@@ -390,3 +406,4 @@ hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int
                                                  float*, float*, hipStream_t);
 INSTANTIATE(float)
 INSTANTIATE(bf16_t)
+INSTANTIATE(f16_t)

@@ -30,6 +30,7 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restric
 // The kernel
 // ---------------------------------------------------------------------------------------------
 // One work-item slot `item` (slot i is dispatched to XCD i % 8) of contraction OP.
-template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, bool F16 = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -525,8 +526,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #define SUBSTEP(fa, fb, READ_, EXTRA_)                                                           \
     do {                                                                                         \
         _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                         \
-            acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                       \
-                fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0);                           \
+            if constexpr (F16)                                                                   \
+                acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(                    \
+                    __builtin_bit_cast(f16x8, fb[m % FN]), __builtin_bit_cast(f16x8, fa[m / FN]), \
+                    acc[m / FN][m % FN], 0, 0, 0);                                               \
+            else                                                                                 \
+                acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                   \
+                    fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0);                       \
             FENCE();                                                                             \
             READ_;                                                                               \
             EXTRA_;                                                                              \
@@ -654,8 +660,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                     if constexpr (OP == OP_FC1 || OP == OP_FC2) {
                         const int gc = min(n0 + wcol0 + col, g.N - 4);   // masked columns read a valid bias
                         const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
-                        v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
-                        v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                        float b0, b1, b2, b3;
+                        unpack2<F16>(bb.x, b0, b1); unpack2<F16>(bb.y, b2, b3);
+                        v[0] += b0; v[1] += b1; v[2] += b2; v[3] += b3;
                     }
                     if constexpr (OUT_F32) {
                         const int c = col >> 2;
@@ -669,21 +676,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) act_both<ACT>(v[r], hh[r], gg[r]);
                             u32x2 pz, hz;
-                            pz.x = pack_bf2(gg[0], gg[1]); pz.y = pack_bf2(gg[2], gg[3]);
-                            hz.x = pack_bf2(hh[0], hh[1]); hz.y = pack_bf2(hh[2], hh[3]);
+                            pz.x = pack2<F16>(gg[0], gg[1]); pz.y = pack2<F16>(gg[2], gg[3]);
+                            hz.x = pack2<F16>(hh[0], hh[1]); hz.y = pack2<F16>(hh[2], hh[3]);
                             *reinterpret_cast<u32x2*>(wreg + off) = pz;
                             *reinterpret_cast<u32x2*>(wreg + 8192 + off) = hz;
                         } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
                             u32x2 z;
-                            z.x = pack_bf2(v[0], v[1]); z.y = pack_bf2(v[2], v[3]);
+                            z.x = pack2<F16>(v[0], v[1]); z.y = pack2<F16>(v[2], v[3]);
                             *reinterpret_cast<u32x2*>(wreg + off) = z;
                         } else {   // DGRAD2
                             const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + 16384 + (i & 1) * 8192 + off);
-                            const float p0 = __uint_as_float(pp.x << 16), p1 = __uint_as_float(pp.x & 0xffff0000u);
-                            const float p2 = __uint_as_float(pp.y << 16), p3 = __uint_as_float(pp.y & 0xffff0000u);
+                            float p0, p1, p2, p3;
+                            unpack2<F16>(pp.x, p0, p1); unpack2<F16>(pp.y, p2, p3);
                             u32x2 d;
-                            d.x = pack_bf2(v[0] * p0, v[1] * p1);
-                            d.y = pack_bf2(v[2] * p2, v[3] * p3);
+                            d.x = pack2<F16>(v[0] * p0, v[1] * p1);
+                            d.y = pack2<F16>(v[2] * p2, v[3] * p3);
                             *reinterpret_cast<u32x2*>(wreg + off) = d;
                         }
                     }
@@ -696,8 +703,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 for (int row = 0; row < 32; ++row) {
                     const uint32_t w2 = *reinterpret_cast<const uint32_t*>(
                         wreg + row * RPB + ((((lane >> 2) ^ (row & 15))) << 4) + (lane & 3) * 4);
-                    cs0 += __uint_as_float(w2 << 16);
-                    cs1 += __uint_as_float(w2 & 0xffff0000u);
+                    float c0, c1;
+                    unpack2<F16>(w2, c0, c1);
+                    cs0 += c0; cs1 += c1;
                 }
             }
             // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
@@ -734,20 +742,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #undef STORE16
 }
 
-template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, bool F16 = false>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
-    gemm_tile<BM, BN, WM, WN, OP, ACT>(g, (int)blockIdx.x);
+    gemm_tile<BM, BN, WM, WN, OP, ACT, F16>(g, (int)blockIdx.x);
 }
 
 // Two independent contractions in one grid (the paper's fused backward kernel, Sec. 3.2 "Fused
 // Kernel in Backward Propagation": the input gradient and the weight gradient of one linear layer
 // do not depend on each other): slots [0, items_a) are contraction OPA's, the rest OPB's, so the
 // tail of one fills with tiles of the other.  items_a is a multiple of 8 (XCD mapping).
-template <int BM, int BN, int WM, int WN, int OPA, int OPB>
+template <int BM, int BN, int WM, int WN, int OPA, int OPB, bool F16 = false>
 __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_pair(GemmArgs ga, GemmArgs gb, int items_a) {
     const int item = (int)blockIdx.x;
-    if (item < items_a) gemm_tile<BM, BN, WM, WN, OPA>(ga, item);
-    else gemm_tile<BM, BN, WM, WN, OPB>(gb, item - items_a);
+    if (item < items_a) gemm_tile<BM, BN, WM, WN, OPA, HEXA_ACT_GELU_TANH, F16>(ga, item);
+    else gemm_tile<BM, BN, WM, WN, OPB, HEXA_ACT_GELU_TANH, F16>(gb, item - items_a);
 }
 
 // Second stage of the split token contraction, plus exact zeros for experts without tokens.
@@ -779,10 +787,10 @@ __global__ __launch_bounds__(256) void wgrad_finish(const int32_t* __restrict__ 
 
 constexpr int kNumCUs = 256;
 
-template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH>
+template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, bool F16 = false>
 void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label) {
     ProfScope ps(st, label);
-    auto kern = gemm_bf16<BM, BN, WM, WN, OP, ACT>;
+    auto kern = gemm_bf16<BM, BN, WM, WN, OP, ACT, F16>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
@@ -797,10 +805,10 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char
 
 // Row GEMM OPA and token contraction OPB of one linear layer's backward in one grid, then the
 // split-K finisher of OPB.
-template <int BM, int BN, int WM, int WN, int OPA, int OPB>
+template <int BM, int BN, int WM, int WN, int OPA, int OPB, bool F16 = false>
 void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipStream_t st,
                  const char* label, const char* label_fin) {
-    auto kern = gemm_bf16_pair<BM, BN, WM, WN, OPA, OPB>;
+    auto kern = gemm_bf16_pair<BM, BN, WM, WN, OPA, OPB, F16>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
     static bool attr_done = false;
     if (!attr_done) {
@@ -862,7 +870,8 @@ size_t wgrad_max_slots(const MoeDims& D) {
     return 2 * (size_t)(D.A / wgrad_chunk_len(D)) + 2;
 }
 
-hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* b1,
+template <bool F16>
+static hipError_t fwd_impl(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* b1,
                            const bf16_t* W2, const bf16_t* b2, const hexa_moe_idx& idx,
                            const MoeWorkspace& ws, hipStream_t st) {
     GemmArgs g{};
@@ -870,15 +879,16 @@ hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
     launch_worklists(D, idx, ws, st);
     g.A = x; g.a_rows = D.T; g.B = W1; g.bias = b1; g.out0 = ws.pre; g.out1 = ws.h; g.K = D.d; g.N = D.f;
-    if (D.act == HEXA_ACT_RELU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_RELU>(D, g, st, "fc1");
-    else if (D.act == HEXA_ACT_SILU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_SILU>(D, g, st, "fc1");
-    else launch_rows<TBM, TBN, TWM, TWN, OP_FC1>(D, g, st, "fc1");
+    if (D.act == HEXA_ACT_RELU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_RELU, F16>(D, g, st, "fc1");
+    else if (D.act == HEXA_ACT_SILU) launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_SILU, F16>(D, g, st, "fc1");
+    else launch_rows<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_GELU_TANH, F16>(D, g, st, "fc1");
     g.A = (const bf16_t*)ws.h; g.B = W2; g.bias = b2; g.out0 = ws.o; g.out1 = nullptr; g.K = D.f; g.N = D.d;
-    launch_rows<TBM, TBN, TWM, TWN, OP_FC2>(D, g, st, "fc2");
+    launch_rows<TBM, TBN, TWM, TWN, OP_FC2, HEXA_ACT_GELU_TANH, F16>(D, g, st, "fc2");
     return hipGetLastError();
 }
 
-hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1, const bf16_t* W2,
+template <bool F16>
+static hipError_t bwd_impl(const MoeDims& D, const bf16_t* xg, const bf16_t* W1, const bf16_t* W2,
                            const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
                            hipStream_t st) {
     GemmArgs g{};
@@ -886,16 +896,31 @@ hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
     launch_worklists(D, idx, ws, st);
-    // 2nd linear layer: dpre = (do W2^T) * GELU'(pre)  and  dW2[e] = h^T do
+    // 2nd linear layer: dpre = (do W2^T) * F'(pre)  and  dW2[e] = h^T do
     GemmArgs r = g, t = g;
     r.A = (const bf16_t*)ws.dout; r.B = W2; r.pre_in = (const bf16_t*)ws.pre; r.out0 = ws.dpre;
     r.colpart = ws.colpart; r.K = D.d; r.N = D.f;
     t.A = (const bf16_t*)ws.h; t.B = (const bf16_t*)ws.dout; t.out0 = dW2; t.M = D.f; t.N = D.d;
-    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD2, OP_WGRAD2>(D, r, t, st, "bwd_fc2", "wgrad2_finish");
+    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD2, OP_WGRAD2, F16>(D, r, t, st, "bwd_fc2", "wgrad2_finish");
     // 1st linear layer: dxp = dpre W1^T  and  dW1[e] = xg^T dpre
     r = g; t = g;
     r.A = (const bf16_t*)ws.dpre; r.B = W1; r.out0 = ws.dxp; r.K = D.f; r.N = D.d;
     t.A = xg; t.B = (const bf16_t*)ws.dpre; t.out0 = dW1; t.M = D.d; t.N = D.f;
-    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD1, OP_WGRAD1>(D, r, t, st, "bwd_fc1", "wgrad1_finish");
+    launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD1, OP_WGRAD1, F16>(D, r, t, st, "bwd_fc1", "wgrad1_finish");
     return hipGetLastError();
+}
+
+// The 16-bit paths: all pointers are raw 16-bit storage, bf16 or (f16 = true) IEEE fp16.
+hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* b1,
+                           const bf16_t* W2, const bf16_t* b2, const hexa_moe_idx& idx,
+                           const MoeWorkspace& ws, hipStream_t st, bool f16) {
+    return f16 ? fwd_impl<true>(D, x, W1, b1, W2, b2, idx, ws, st)
+               : fwd_impl<false>(D, x, W1, b1, W2, b2, idx, ws, st);
+}
+
+hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1, const bf16_t* W2,
+                           const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
+                           hipStream_t st, bool f16) {
+    return f16 ? bwd_impl<true>(D, xg, W1, W2, idx, ws, dW1, dW2, st)
+               : bwd_impl<false>(D, xg, W1, W2, idx, ws, dW1, dW2, st);
 }

@@ -30,7 +30,7 @@ class MoEWorkload:
     d_ff: int       # hidden size between the two MLPs
     E: int          # global experts
     k: int          # top-k
-    dtype: str      # "f32" | "bf16"
+    dtype: str      # "f32" | "bf16" | "f16"
     routing: str    # recipe name, see _route()
     seed: int
 
@@ -121,7 +121,7 @@ def generate(w: MoEWorkload, device="cpu") -> Dict[str, torch.Tensor]:
     device = torch.device(device)
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
-    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[w.dtype]
     out = {}
     out["topk_idx"], out["gate"] = _route(w, gen, device)
     out["x"] = _randn((w.T, w.d_model), gen, device).to(tdt)
