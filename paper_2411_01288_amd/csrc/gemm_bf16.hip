@@ -64,22 +64,20 @@ struct GemmArgs {
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// r = 1 / (1 + exp(2 s)),  s = sqrt(2/pi) (u + 0.044715 u^3):  tanh(s) = 1 - 2 r.
-// exp(2 s) = 2^(u (k1 + k3 u^2)) with log2(e) folded into the two constants.
-__device__ __forceinline__ float gelu_r(float u) {
-    constexpr float k1 = 2.f * HEXA_GELU_C * 1.4426950408889634f;
-    constexpr float k3 = k1 * HEXA_GELU_A;
-    return fast_rcp(1.f + fast_exp2(u * (k1 + k3 * (u * u))));
-}
-// h = GELU(u) = u (1 - r) and g = GELU'(u) = (1 - r) (1 + 2 u r C (1 + 3 A u^2)) from one r
+// s = 1 / (1 + exp(-2 t)),  t = sqrt(2/pi) (u + 0.044715 u^3):  tanh(t) = 2 s - 1, GELU(u) = u s.
+// exp(-2 t) = 2^(u (k1 + k3 u^2)) with -log2(e) folded into the two constants.
+// h = GELU(u) = u s and g = GELU'(u) = s + u s (1 - s) 2C (1 + 3 A u^2) from one s: eight
+// full-rate operations and two transcendental ones
 // (App. B Table 5 rows 2 and 7 need both; the forward epilogue has u in registers, so it saves g
 // for the backward pass instead of u itself: same bytes, and the backward epilogue is one multiply).
 __device__ __forceinline__ void gelu_both(float u, float& h, float& g) {
-    const float r = gelu_r(u);
-    const float ur = u * r;
-    h = u - ur;
-    const float t = 1.f + ur * (2.f * HEXA_GELU_C + 6.f * HEXA_GELU_C * HEXA_GELU_A * (u * u));
-    g = (1.f - r) * t;
+    constexpr float k1 = -2.f * HEXA_GELU_C * 1.4426950408889634f;
+    constexpr float k3 = k1 * HEXA_GELU_A;
+    const float u2 = u * u;
+    const float s = fast_rcp(1.f + fast_exp2(u * (k1 + k3 * u2)));
+    h = u * s;
+    const float q = 2.f * HEXA_GELU_C + 6.f * HEXA_GELU_C * HEXA_GELU_A * u2;
+    g = s + (h - h * s) * q;
 }
 
 // The same pair for the other activations: ReLU (derivative 0 at 0) and SiLU u s(u), s = 1/(1+e^-u),
