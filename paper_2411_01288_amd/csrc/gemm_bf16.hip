@@ -15,7 +15,7 @@
 // expert's weights; rows are addressed through the re-index vector, so nothing is padded to a
 // capacity and nothing is dropped.  What is not: the 16x16x16 warp tiles, the per-expert serial
 // loop of Alg. 4 and the padded (-1) re-index vector.  Here a workgroup owns a 256x256 tile,
-// each 64-lane wavefront a grid of 32x32x16 bf16 MFMA blocks, operands go from
+// each 64-lane wavefront a grid of 16x16x32 bf16 MFMA blocks, operands go from
 // global memory straight into LDS (no registers in between) as [row][64 k] with a 16-byte XOR
 // swizzle (conflict-free 128-bit reads); operands whose contraction index is the slow one in
 // memory (weights in the forward GEMMs, both operands of the token contractions) keep their
@@ -31,7 +31,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -98,7 +98,7 @@ __device__ __forceinline__ void act_both(float u, float& h, float& g) {
 
 // LDS image of a K-contiguous operand: row r = BK*2 = 128 bytes = CPRK chunks of 16 bytes (8 bf16
 // along k); chunk c of row r sits at position c ^ key(r).  gfx950's LDS serves 128-bit reads 16 lanes
-// (256 bytes, 64 banks) per clock; a 32x32x16 fragment read has 16 consecutive lanes on 16
+// (256 bytes, 64 banks) per clock; a 16x16x32 fragment read has 16 consecutive lanes on 16
 // consecutive rows with one chunk index.  Two consecutive 128-byte rows fill the 256 bytes of bank
 // space, so rows r, r+2, ..., r+14 must sit on eight different chunk positions:
 // key(r) = (r >> 1) & 7.
@@ -194,29 +194,39 @@ struct StageKC {
 };
 
 // K-strided operand (BK k-rows x R columns, a k-row is R*2 contiguous bytes in memory).
-// LDS image: k-row k at k*R*2, 16-byte chunk c (8 columns) at position c ^ ((k & 3) << 2).
-// It is read with ds_read_b64_tr_b16, which hands each lane four k-values of one column; the key
-// puts the four k-rows one 16-lane group touches on four different quarters of the bank space.
+// LDS image: k-row k at k*R*2, 16-byte chunk c (8 columns) at position c ^ ks_key(k).
+// It is read with ds_read_b64_tr_b16, which hands each lane four k-values of one column; a
+// 32-lane half of such a read touches k-rows {8a + j, 8(a+1) + j : j < 4}, 32 bytes (16 columns) of
+// each, and the key puts those eight pieces on the eight 32-byte slots of the bank space.
 // Instruction q fills k-rows RPI*q .. RPI*q + RPI-1 (RPI = 512 / R rows of R*2 bytes).
+__device__ __forceinline__ int ks_key(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
+
 template <int R, int NW>
 struct StageKS {
     static constexpr int RB = R * 2;            // bytes per k-row
     static constexpr int CPR = RB / 16;         // chunks per k-row
     static constexpr int RPI = 1024 / RB;       // k-rows per instruction
-    static constexpr int NI = BK / RPI / NW;    // instructions per wave and stage
-    static_assert(RPI >= 1 && (BK / RPI) % NW == 0 && (RPI * NW) % 4 == 0 && CPR >= 16, "unsupported staging shape");
-    struct Lane { uint32_t voff; };             // byte offset of this lane's first fetch
+    static constexpr int NI = BK / RPI / NW;    // instructions per wave and block
+    static_assert(RPI >= 1 && (BK / RPI) % NW == 0 && RPI * NW == 8 && CPR >= 16, "unsupported staging shape");
+    // instruction i of a wave covers k-rows RPI*wave + kin + 8 i: (k & 3) is the same for all i and
+    // ((k >> 3) & 1) = i & 1, so a lane needs two offsets (even and odd i)
+    struct Lane { uint32_t voff[2]; };
     __device__ static __forceinline__ Lane lane_init(int wave, int lane, uint32_t ld_bytes, int col0) {
         const int kin = lane / CPR;                          // k-row inside the instruction
-        const int k = (RPI * wave + kin);                    // k-row of instruction i = 0
-        const int c = (lane % CPR) ^ ((k & 3) << 2);         // (RPI*NW*i is a multiple of 4)
-        return Lane{(uint32_t)k * ld_bytes + (uint32_t)(col0 + 8 * c) * 2u};
+        const int k = (RPI * wave + kin);                    // k-row of instruction i = 0  (< 8)
+        Lane ln;
+#pragma unroll
+        for (int odd = 0; odd < 2; ++odd) {
+            const int c = (lane % CPR) ^ ks_key(k + 8 * odd);
+            ln.voff[odd] = (uint32_t)k * ld_bytes + (uint32_t)(col0 + 8 * c) * 2u;
+        }
+        return ln;
     }
     __device__ static __forceinline__ void prep(uint32_t lds_slot, int wave, int i) {
         dtl_m0(lds_slot + (uint32_t)(wave + NW * i) * 1024u);
     }
     __device__ static __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t ld_bytes, const Lane& ln, int i) {
-        dtl_load(r, ln.voff, soff + (uint32_t)(RPI * NW * i) * ld_bytes);
+        dtl_load(r, ln.voff[i & 1], soff + (uint32_t)(RPI * NW * i) * ld_bytes);
     }
 };
 
@@ -286,19 +296,19 @@ template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, 
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
-    constexpr int FM = TM / 32, FN = TN / 32;
+    constexpr int FM = TM / 16, FN = TN / 16;   // 16x16 MFMA blocks per wave tile
     constexpr bool TOKENS = (OP == OP_WGRAD2 || OP == OP_WGRAD1);
     constexpr bool B_KS = TOKENS || OP == OP_FC1 || OP == OP_FC2;
     constexpr int SLOT = (BM > BN ? BM : BN) * ROWB;   // bytes of one ring slot (one operand, one block)
-    constexpr int SPS = BK / 16;              // k-substeps (one MFMA k each) per block
-    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of 32x32");
+    constexpr int SPS = BK / 32;              // k-substeps (one MFMA k = 32 each) per block
+    static_assert(TM % 16 == 0 && TN % 16 == 0, "wave tile must be a multiple of 16x16");
 
     extern __shared__ __align__(1024) uint8_t smem[];   // the slot ring; reused by the epilogue
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int l32 = lane & 31, hi = lane >> 5;
+    const int l16 = lane & 15, grp = lane >> 4;   // MFMA lane coordinates
 
     // ---- which work item ------------------------------------------------------------------
     int e, m0, n0, mvalid, nk;
@@ -406,148 +416,146 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #define LOAD_A(kt_, i_) SA::load(ra, (kt_) * a_step, a_row, lna, i_)
 #define LOAD_B(kt_, i_) SB::load(rb, (kt_) * b_step, b_row, lnb, i_)
 
-    f32x16 acc[FM][FN];
+    f32x4 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- per-lane fragment addresses -----------------------------------------------------------
-    // K-contiguous image: 128-bit read of row (wave tile row + l32), chunk (2s + hi) ^ key(l32)
-    // (wave tile rows and fragment rows are multiples of 32, so key(row) = key(l32)).
-    // K-strided image: two transposing 64-bit reads per fragment; in a group of 16 lanes, lane s
-    // addresses k-row (s >> 2) and columns 4*(s & 3).., and receives column (s) of the group's 16,
-    // k-rows 0..3 (see StageKS).  Both give a lane k = 16s + 8hi + 0..7 of its row/column.
+    // A 16x16x32 MFMA operand fragment: lane (l16, grp) holds k = 8*grp + 0..7 of row (or column) l16
+    // of its 16-wide block.
+    // K-contiguous image: one 128-bit read of row (block row + l16), chunk (4*sub + grp) ^ key(l16)
+    // (wave-tile and block rows are multiples of 16, so key(row) = key(l16)).
+    // K-strided image: two transposing 64-bit reads per fragment.  In a group of 16 lanes, lane s
+    // addresses k-row (s >> 2) and columns 4*(s & 3).., and receives column s of the block's 16,
+    // k-rows 0..3; group grp reads k-rows 32*sub + 8*grp + 4*half + 0..3 (see StageKS).
     constexpr int A_RB = BM * 2, B_RB = BN * 2;  // LDS k-row pitch of the K-strided images
-    uint32_t aoff[4], boff[4];                   // KC: per k-substep; KS: per fragment
-    uint32_t a_ks = 0, b_ks = 0;                 // KS lane base
+    // KC: aoff[sub] = byte offset of this lane's chunk in block row 0.
+    // KS: one lane constant a_l0: k-row part | within-chunk byte | (chunk of block 0 ^ key) << 4.
+    // Block q's chunk index differs from block 0's in bits 1..3 only (2q), the bits the key works
+    // on, so its offset is a_l0 ^ (q << 5); the k-row of (substep, half) is an immediate.
+    uint32_t aoff[SPS], boff[SPS];
+    uint32_t a_l0 = 0, b_l0 = 0;
     {
-        const int s16 = lane & 15, grp = lane >> 4;
-        const int krel = s16 >> 2, dlt = 2 * (grp & 1) + ((s16 & 3) >> 1), half8 = (s16 & 1) * 8;
+        const int krel = l16 >> 2, pair = (l16 & 3) >> 1, half8 = (l16 & 1) * 8;
+        const int key = ks_key(8 * grp + krel);  // the key of every k-row this lane reads
+        static_assert(A_RB % 512 == 0 && B_RB % 512 == 0 && TM % 128 == 0 && TN % 128 == 0, "bit fields of the K-strided fragment offset");
         if constexpr (TOKENS) {
-            a_ks = (uint32_t)((8 * hi + krel) * A_RB + dlt * 16 + half8);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                aoff[i] = (uint32_t)((((wm * TM) / 8 + 4 * i) ^ (krel << 2)) * 16);
+            a_l0 = (uint32_t)((8 * grp + krel) * A_RB + half8 + ((((wm * TM) / 8 + pair) ^ key) << 4));
         } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                aoff[s] = (uint32_t)((wm * TM + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
+            for (int sb = 0; sb < SPS; ++sb)
+                aoff[sb] = (uint32_t)((wm * TM + l16) * ROWB) + (uint32_t)(((4 * sb + grp) ^ lds_swz(l16)) << 4);
         }
         if constexpr (B_KS) {
-            b_ks = (uint32_t)((8 * hi + krel) * B_RB + dlt * 16 + half8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                boff[j] = (uint32_t)((((wn * TN) / 8 + 4 * j) ^ (krel << 2)) * 16);
+            b_l0 = (uint32_t)((8 * grp + krel) * B_RB + half8 + ((((wn * TN) / 8 + pair) ^ key) << 4));
         } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                boff[s] = (uint32_t)((wn * TN + l32) * ROWB) + (uint32_t)((((2 * s + hi) % CPRK) ^ lds_swz(l32)) << 4);
+            for (int sb = 0; sb < SPS; ++sb)
+                boff[sb] = (uint32_t)((wn * TN + l16) * ROWB) + (uint32_t)(((4 * sb + grp) ^ lds_swz(l16)) << 4);
         }
     }
-    static_assert(FM <= 4 && FN <= 4, "fragment offset tables hold four entries");
 
-    // two fragment sets: set (s & 1) is multiplied while the other one is being read
+    // two fragment sets: one is multiplied while the other one is being read (a read never targets
+    // registers an MFMA in flight may still be reading)
     bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define TR_READ(p_) __builtin_bit_cast(s16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p_)))
-    // LDS reads of one k-substep are numbered: A fragments first, then B fragments; a K-strided
-    // fragment takes two reads (k-rows +0..3 and +4..7), a K-contiguous one takes one.
+#define TR_JOIN(lo_, p_) __builtin_bit_cast(bf16x8, __builtin_shufflevector((lo_), TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7))
+    // The MFMAs of a substep run A-fragment-major (MFMA m = A fragment m / FN x B fragment m % FN),
+    // so the next substep needs A fragment 0 and every B fragment first: its LDS reads are numbered
+    // A0, B0 .. B(FN-1), A1 .. A(FM-1); a K-strided fragment takes two reads (k-rows +0..3 and
+    // +4..7), a K-contiguous one takes one.
     constexpr int RA = TOKENS ? 2 : 1, RBn = B_KS ? 2 : 1;
     constexpr int NRD = FM * RA + FN * RBn;
-    s16x4 tra[FM], trb[FN];   // first halves of K-strided fragments
-    // read number m_ of k-substep s_ from the slots at ab_ (A image) and bb_ (B image)
-#define READ_ONE(fa, fb, ab_, bb_, s_, m_)                                                       \
+    s16x4 trt;   // first half of the K-strided fragment being read
+#define READ_A(fa, ab_, s_, q_, h_)                                                              \
     do {                                                                                         \
-        if ((m_) < FM * RA) {                                                                    \
-            const int i_ = (m_) / RA;                                                            \
-            if constexpr (TOKENS) {                                                              \
-                const uint8_t* p_ = (ab_) + a_ks + aoff[i_] + (16 * (s_) + 4 * ((m_) % RA)) * A_RB; \
-                if ((m_) % RA == 0) tra[i_] = TR_READ(p_);                                       \
-                else fa[i_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(tra[i_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
-            } else {                                                                             \
-                fa[i_] = *reinterpret_cast<const bf16x8*>((ab_) + aoff[s_] + i_ * 32 * ROWB);     \
-            }                                                                                    \
-        } else if ((m_) < NRD) {                                                                 \
-            const int mb_ = (m_) - FM * RA;                                                      \
-            const int j_ = mb_ / RBn;                                                            \
-            if constexpr (B_KS) {                                                                \
-                const uint8_t* p_ = (bb_) + b_ks + boff[j_] + (16 * (s_) + 4 * (mb_ % RBn)) * B_RB; \
-                if (mb_ % RBn == 0) trb[j_] = TR_READ(p_);                                       \
-                else fb[j_] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(trb[j_], TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7)); \
-            } else {                                                                             \
-                fb[j_] = *reinterpret_cast<const bf16x8*>((bb_) + boff[s_] + j_ * 32 * ROWB);     \
-            }                                                                                    \
+        if constexpr (TOKENS) {                                                                  \
+            const uint8_t* p_ = (ab_) + (a_l0 ^ (uint32_t)((q_) << 5)) + (32 * (s_) + 4 * (h_)) * A_RB; \
+            if ((h_) == 0) trt = TR_READ(p_);                                                    \
+            else fa[q_] = TR_JOIN(trt, p_);                                                      \
+        } else {                                                                                 \
+            fa[q_] = *reinterpret_cast<const bf16x8*>((ab_) + aoff[s_] + (q_) * 16 * ROWB);       \
         }                                                                                        \
+    } while (0)
+#define READ_B(fb, bb_, s_, q_, h_)                                                              \
+    do {                                                                                         \
+        if constexpr (B_KS) {                                                                    \
+            const uint8_t* p_ = (bb_) + (b_l0 ^ (uint32_t)((q_) << 5)) + (32 * (s_) + 4 * (h_)) * B_RB; \
+            if ((h_) == 0) trt = TR_READ(p_);                                                    \
+            else fb[q_] = TR_JOIN(trt, p_);                                                      \
+        } else {                                                                                 \
+            fb[q_] = *reinterpret_cast<const bf16x8*>((bb_) + boff[s_] + (q_) * 16 * ROWB);       \
+        }                                                                                        \
+    } while (0)
+    // read number r_ of k-substep s_ from the slots at ab_ (A image) and bb_ (B image)
+#define READ_ONE(fa, fb, ab_, bb_, s_, r_)                                                       \
+    do {                                                                                         \
+        if ((r_) < RA) READ_A(fa, ab_, s_, 0, (r_));                                             \
+        else if ((r_) < RA + FN * RBn) READ_B(fb, bb_, s_, ((r_) - RA) / RBn, ((r_) - RA) % RBn); \
+        else if ((r_) < NRD) READ_A(fa, ab_, s_, 1 + ((r_) - RA - FN * RBn) / RA, ((r_) - RA - FN * RBn) % RA); \
     } while (0)
 
     constexpr int NM = FM * FN;   // MFMAs per k-substep and wave
-    static_assert(NRD <= NM, "fragment reads must fit the substep");
-    static_assert(SPS == 4, "the schedule below is written for four k-substeps per block");
+    // Read r goes into memory slot (RSPAN * r) / NRD: the reads end a quarter substep before the
+    // substep does, because the wave waits for all of them at the block barrier and at the loop head
+    // (where the compiler merges its counters), and an LDS read issued just before would be waited
+    // for in full.
+    constexpr int RSPAN = NM * 3 / 4;
+    static_assert(FM == 8 && FN == 8 && NRD <= RSPAN, "the issue slots are laid out for an 8 x 8 block grid");
+    static_assert(SPS == 2, "the schedule below is written for two k-substeps per block");
     constexpr int NIA = SA::NI, NIB = SB::NI;    // staging instructions per wave, operand and block
-    // A staging request takes two issue slots: its set-up after one MFMA, its load after the next.
-    // Operand A's NIA requests are spread over substeps 0 and 1 (request o: global slots o*ASTR+1,
-    // o*ASTR+2); operand B's NIB requests follow the block barrier in substep 3 (request o: slots
-    // BSKIP + o*BSTR, + 1; with BSTR = 1 a slot holds the load of one request and then the set-up of
-    // the next, which is fine: the load has read M0 by then).  The first slots after the barrier stay free so that a write into the
-    // slot block j's A image leaves can only land (>= 250 cycles of L2 latency later) well after
-    // the other waves' last fragment reads of that image, issued before the barrier, have drained
-    // from the LDS queue.
-    constexpr int ASTR = 2 * NM / NIA;
-    constexpr int BSKIP = 2, BSTR = (NM - BSKIP) / NIB;
-    static_assert((2 * NM) % NIA == 0 && ASTR >= 3 && BSTR >= 1 && BSKIP + BSTR * (NIB - 1) + 1 < NM,
-                  "staging requests must fit the issue slots");
-#define STAGE_A_AT(g_, slot_, kt_)                                                               \
+    static_assert(NIA == 8 && NIB == 8, "one staging request per eight MFMAs");
+    // A 16-cycle MFMA leaves the wave three more issue cycles, so no memory slot may hold more than
+    // three instructions: fragment reads are spread evenly over the first three quarters, staging request o sits in the slots
+    // 8 o + 1 (M0 set-up) and 8 o + 3 (load; the MFMA in between is the wait state M0 needs).
+    // Operand A's requests go into substep 0, operand B's follow the block barrier in substep 1:
+    // every wave has waited for its own fragment reads of the slot that is refilled (lgkmcnt) before
+    // that barrier.
+#define STAGE_AT(m_, PREP_, LOAD_, slot_, kt_)                                                   \
     do {                                                                                         \
-        _Pragma("unroll") for (int o = 0; o < NIA; ++o) {                                        \
-            if (o * ASTR + 1 == (g_)) PREP_A(slot_, o);                                          \
-            if (o * ASTR + 2 == (g_)) LOAD_A(kt_, o);                                            \
-        }                                                                                        \
-    } while (0)
-#define STAGE_B_AT(m_, slot_, kt_)                                                               \
-    do {                                                                                         \
-        _Pragma("unroll") for (int o = 0; o < NIB; ++o) {                                        \
-            if (o * BSTR + BSKIP + 1 == (m_)) LOAD_B(kt_, o);                                    \
-            if (o * BSTR + BSKIP == (m_)) PREP_B(slot_, o);                                      \
-        }                                                                                        \
+        if ((m_) % 8 == 1) PREP_(slot_, (m_) / 8);                                               \
+        if ((m_) % 8 == 3) LOAD_(kt_, (m_) / 8);                                                 \
     } while (0)
     // The MFMA gets the B fragment as its first and the A fragment as its second operand (both
-    // have the same lane layout), so each 32x32 block comes out transposed: a lane then holds ONE
-    // tile row (l32) and 4 consecutive tile columns per register quad, which the epilogue stores
-    // as 8- or 16-byte vectors.
+    // have the same lane layout), so each 16x16 block comes out transposed: a lane then holds ONE
+    // block row (l16) and the 4 consecutive block columns 4*grp + 0..3, which the epilogue stores
+    // as 8- or 16-byte vectors.  (16x16x32 rather than 32x32x16: the same FLOP per cycle, but the
+    // accumulator traffic per FLOP is half, and under the part's power limit the clock settles
+    // higher.)
     // One k-substep: NM MFMAs on fragment set (fa, fb); after MFMA m, memory slot m is issued
-    // (one fragment read for the next substep, and at most one staging instruction), so the
+    // (at most one fragment read for the next substep or one half of a staging request), so the
     // LDS and vector-memory queues are fed a little at a time while the matrix pipe stays busy:
     // one wavefront per SIMD has nobody else to hide a burst behind.
 #define SUBSTEP(fa, fb, READ_, EXTRA_)                                                           \
     do {                                                                                         \
         _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                         \
             if constexpr (F16)                                                                   \
-                acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(                    \
-                    __builtin_bit_cast(f16x8, fb[m % FN]), __builtin_bit_cast(f16x8, fa[m / FN]), \
-                    acc[m / FN][m % FN], 0, 0, 0);                                               \
+                asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0"                            \
+                             : "+a"(acc[m / FN][m % FN]) : "v"(fb[m % FN]), "v"(fa[m / FN]));    \
             else                                                                                 \
-                acc[m / FN][m % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                   \
-                    fb[m % FN], fa[m / FN], acc[m / FN][m % FN], 0, 0, 0);                       \
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                           \
+                             : "+a"(acc[m / FN][m % FN]) : "v"(fb[m % FN]), "v"(fa[m / FN]));    \
             FENCE();                                                                             \
-            READ_;                                                                               \
+            _Pragma("unroll") for (int r = 0; r < NRD; ++r)                                      \
+                if ((RSPAN * r) / NRD == m) { READ_; }                                           \
             EXTRA_;                                                                              \
             FENCE();                                                                             \
         }                                                                                        \
     } while (0)
     static_assert(NIA + NIB <= 63, "vmcnt is a 6-bit counter");
 
-    // The K loop runs in blocks of BK = 64 (four k-substeps): a row of a K-contiguous operand is
+    // The K loop runs in blocks of BK = 64 (two k-substeps): a row of a K-contiguous operand is
     // then one whole 128-byte line per block, and the texture-address path, which pays per line
     // touched, moves twice the bytes it would with 32-k stages.  One block of one operand (32 KB)
     // is a ring slot; the five slots of the 160 KB LDS hold, in request order,
     //     A(j) B(j) | A(j+1) B(j+1) A(j+2)       block j being multiplied | requested ahead
     // i.e. half-block h (A(j): h = 2j, B(j): h = 2j+1) lives in slot h % 5.
-    // During block j: substeps 0-1 request A(j+2) into the slot B(j-1) left; before substep 3 the
+    // During block j: substep 0 requests A(j+2) into the slot B(j-1) left; before substep 1 the
     // wave waits until only that request is outstanding (so A(j+1), B(j+1) are complete) and the
-    // barrier publishes them; every fragment read of block j has been issued by then, so substep 3
+    // barrier publishes them; every fragment read of block j has completed by then, so substep 1
     // requests B(j+2) into A(j)'s slot while it reads the first fragments of block j+1.  Past the
     // last block the requests re-fetch the last block into slots nobody reads, which keeps the
     // loop body free of branches.
@@ -561,7 +569,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA + NIB) : "memory");
     __syncthreads();
-    _Pragma("unroll") for (int m = 0; m < NRD; ++m) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, m);
+    _Pragma("unroll") for (int r = 0; r < NRD; ++r) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, r);
 
     int sa = 0, sb = 1;                           // slots of A(j), B(j)
     for (int j = 0; j < nk; ++j) {
@@ -576,21 +584,29 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         const uint32_t b2 = smem0 + (uint32_t)(sa * SLOT);    // B(j+2): the slot of A(j)
         const uint32_t kreq = (uint32_t)min(j + 2, klast);
         FENCE();
-        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, m), STAGE_A_AT(m, a2, kreq));
-        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, abase, bbase, 2, m), STAGE_A_AT(NM + m, a2, kreq));
-        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 3, m), (void)0);
+        SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, r), STAGE_AT(m, PREP_A, LOAD_A, a2, kreq));
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
         __syncthreads();
         FENCE();
-        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, m), STAGE_B_AT(m, b2, kreq));
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, r), STAGE_AT(m, PREP_B, LOAD_B, b2, kreq));
         sa = sa1; sb = sb1;
     }
     // no staging write may still be in flight when the workgroup gives its LDS back
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#undef STAGE_A_AT
-#undef STAGE_B_AT
+    // (the MFMAs are inline assembly, so the compiler does not count the wait states their results
+    // need before the epilogue reads the accumulators: 16 idle cycles cover the 4-pass MFMA)
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    // pin every accumulator to its accumulation register at the loop exit (keeps the register
+    // allocator from shuffling them where the loop and the zero-trip path meet)
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jj = 0; jj < FN; ++jj) asm volatile("" : "+a"(acc[i][jj]));
+#undef STAGE_AT
 #undef SUBSTEP
 #undef READ_ONE
+#undef READ_A
+#undef READ_B
+#undef TR_JOIN
 #undef TR_READ
 #undef FENCE
 #undef PREP_A
@@ -599,41 +615,44 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #undef LOAD_B
 
     // ---- epilogue ------------------------------------------------------------------------------
-    // In block (i, j) a lane holds row i*32 + l32 and, in register quad q, the four columns
-    // j*32 + 8q + 4hi + 0..3.  Stored from there, a wave instruction would touch 32 rows with 8 or
-    // 16 bytes each.  Instead each wave turns one 32-row band (i) at a time through its own 32 KB
-    // of the (now idle) stage ring: vectors are written at [row][chunk ^ row] (16-byte chunks, so
-    // both directions are conflict-free), read back with a lane per 16-byte chunk of a row, and
-    // leave as full 256- or 512-byte row segments.  DGRAD2's saved activation derivatives come in the
-    // same way, staged one band ahead.
+    // In block (i, j) a lane holds row i*16 + l16 and the four columns j*16 + 4*grp + 0..3.  Stored
+    // from there, a wave instruction would touch 16 rows with 8 or 16 bytes each.  Instead each
+    // wave turns one 16-row band (i) at a time through its own 32 KB of the (now idle) ring:
+    // vectors are written at [row][chunk ^ row] (16-byte chunks, so both directions are
+    // conflict-free), read back with a lane per 16-byte chunk of a row, and leave as full 256- or
+    // 512-byte row segments.  DGRAD2's saved activation derivatives come in the same way, staged
+    // one band ahead.
     __syncthreads();   // every wave is done reading fragments
 #define STORE16(p_, v_) (*reinterpret_cast<u32x4*>(p_) = (v_))
     {
         uint8_t* wreg = smem + uwave * 32768;
-        constexpr bool OUT_F32 = TOKENS;   // weight gradients; every activation-like output is bf16
+        constexpr bool OUT_F32 = TOKENS;   // weight gradients; every activation-like output is 16-bit
         constexpr int ESZ = OUT_F32 ? 4 : 2;
         constexpr int RPB = TN * ESZ;                 // bytes per staged row (TN columns)
         constexpr int CPRO = RPB / 16;                // 16-byte chunks per staged row
+        constexpr int BAND = 16;                      // rows per band = rows of an MFMA block
+        constexpr int H_OFF = 8192;                   // FC1: second output band
+        constexpr int G_OFF = 16384, G_BUF = BAND * 256;   // DGRAD2: two bands of saved derivatives
         static_assert(TN == 128, "epilogue staging is laid out for 128-column wave tiles");
         const size_t ldo = (size_t)g.N;
         const int wrow0 = wm * TM, wcol0 = wn * TN;
-        // DGRAD2: stage the saved GELU'(pre)[band][128 cols] (bf16, 256 B rows, chunk ^ (row & 15)) with direct loads
+        // DGRAD2: stage the saved F'(pre)[band][128 cols] (16-bit, 256 B rows, chunk ^ (row & 15))
+        // with direct loads; instruction t covers rows 4t..4t+3
+        constexpr int GI = BAND / 4;                  // staging instructions per band
         rsrc_t rp;
         uint32_t pre_voff = 0;
         if constexpr (OP == OP_DGRAD2) {
             rp = make_rsrc(g.pre_in + (size_t)m0 * ldo, (uint32_t)mvalid * (uint32_t)ldo * 2u);
-            const int prow = lane >> 4, ppos = lane & 15;          // instr t covers rows 4t..4t+3
-            pre_voff = (uint32_t)((wrow0 + prow) * (int)ldo + n0 + wcol0) * 2u;
-            (void)ppos;
+            pre_voff = (uint32_t)((wrow0 + (lane >> 4)) * (int)ldo + n0 + wcol0) * 2u;
         }
         auto stage_pre = [&](int band, int buf) {
             if constexpr (OP == OP_DGRAD2) {
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
+                for (int t = 0; t < GI; ++t) {
                     const int row = 4 * t + (lane >> 4);
                     const int c = (lane & 15) ^ (row & 15);
-                    dtl16(rp, wreg + 16384 + buf * 8192 + t * 1024,
-                          pre_voff + (uint32_t)((band * 32 + 4 * t) * (int)ldo + c * 8) * 2u, 0u);
+                    dtl16(rp, wreg + G_OFF + buf * G_BUF + t * 1024,
+                          pre_voff + (uint32_t)((band * BAND + 4 * t) * (int)ldo + c * 8) * 2u, 0u);
                 }
             }
         };
@@ -642,55 +661,52 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             if constexpr (OP == OP_DGRAD2) {
+                // the next band's derivatives are requested before this band's are awaited; the
+                // counter also holds the previous band's stores, which are older than both
                 if (i + 1 < FM) stage_pre(i + 1, (i + 1) & 1);
-                if (i + 1 < FM) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                if (i + 1 < FM) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GI) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
             // -- registers -> LDS band
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
+                const int col = j * 16 + 4 * grp;                  // column inside the wave tile
+                f32x4 v = acc[i][j];
+                if constexpr (OP == OP_FC1 || OP == OP_FC2) {
+                    const int gc = min(n0 + wcol0 + col, g.N - 4);   // masked columns read a valid bias
+                    const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
+                    float b0, b1, b2, b3;
+                    unpack2<F16>(bb.x, b0, b1); unpack2<F16>(bb.y, b2, b3);
+                    v[0] += b0; v[1] += b1; v[2] += b2; v[3] += b3;
+                }
+                if constexpr (OUT_F32) {
+                    const int c = col >> 2;
+                    *reinterpret_cast<float4*>(wreg + l16 * RPB + ((c ^ l16) << 4)) =
+                        make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+                    const int c = col >> 3;
+                    const uint32_t off = (uint32_t)(l16 * RPB + ((c ^ l16) << 4) + (grp & 1) * 8);
+                    if constexpr (OP == OP_FC1) {
+                        float hh[4], gg[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = j * 32 + 8 * q + 4 * hi;       // column inside the wave tile
-                    float v[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
-                    if constexpr (OP == OP_FC1 || OP == OP_FC2) {
-                        const int gc = min(n0 + wcol0 + col, g.N - 4);   // masked columns read a valid bias
-                        const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
-                        float b0, b1, b2, b3;
-                        unpack2<F16>(bb.x, b0, b1); unpack2<F16>(bb.y, b2, b3);
-                        v[0] += b0; v[1] += b1; v[2] += b2; v[3] += b3;
-                    }
-                    if constexpr (OUT_F32) {
-                        const int c = col >> 2;
-                        *reinterpret_cast<float4*>(wreg + l32 * RPB + ((c ^ (l32 & (CPRO - 1))) << 4)) =
-                            make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        const int c = col >> 3;
-                        const uint32_t off = (uint32_t)(l32 * RPB + ((c ^ (l32 & (CPRO - 1))) << 4) + hi * 8);
-                        if constexpr (OP == OP_FC1) {
-                            float hh[4], gg[4];
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) act_both<ACT>(v[r], hh[r], gg[r]);
-                            u32x2 pz, hz;
-                            pz.x = pack2<F16>(gg[0], gg[1]); pz.y = pack2<F16>(gg[2], gg[3]);
-                            hz.x = pack2<F16>(hh[0], hh[1]); hz.y = pack2<F16>(hh[2], hh[3]);
-                            *reinterpret_cast<u32x2*>(wreg + off) = pz;
-                            *reinterpret_cast<u32x2*>(wreg + 8192 + off) = hz;
-                        } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
-                            u32x2 z;
-                            z.x = pack2<F16>(v[0], v[1]); z.y = pack2<F16>(v[2], v[3]);
-                            *reinterpret_cast<u32x2*>(wreg + off) = z;
-                        } else {   // DGRAD2
-                            const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + 16384 + (i & 1) * 8192 + off);
-                            float p0, p1, p2, p3;
-                            unpack2<F16>(pp.x, p0, p1); unpack2<F16>(pp.y, p2, p3);
-                            u32x2 d;
-                            d.x = pack2<F16>(v[0] * p0, v[1] * p1);
-                            d.y = pack2<F16>(v[2] * p2, v[3] * p3);
-                            *reinterpret_cast<u32x2*>(wreg + off) = d;
-                        }
+                        for (int r = 0; r < 4; ++r) act_both<ACT>(v[r], hh[r], gg[r]);
+                        u32x2 pz, hz;
+                        pz.x = pack2<F16>(gg[0], gg[1]); pz.y = pack2<F16>(gg[2], gg[3]);
+                        hz.x = pack2<F16>(hh[0], hh[1]); hz.y = pack2<F16>(hh[2], hh[3]);
+                        *reinterpret_cast<u32x2*>(wreg + off) = pz;
+                        *reinterpret_cast<u32x2*>(wreg + H_OFF + off) = hz;
+                    } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
+                        u32x2 z;
+                        z.x = pack2<F16>(v[0], v[1]); z.y = pack2<F16>(v[2], v[3]);
+                        *reinterpret_cast<u32x2*>(wreg + off) = z;
+                    } else {   // DGRAD2
+                        const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + G_OFF + (i & 1) * G_BUF + off);
+                        float p0, p1, p2, p3;
+                        unpack2<F16>(pp.x, p0, p1); unpack2<F16>(pp.y, p2, p3);
+                        u32x2 d;
+                        d.x = pack2<F16>(v[0] * p0, v[1] * p1);
+                        d.y = pack2<F16>(v[2] * p2, v[3] * p3);
+                        *reinterpret_cast<u32x2*>(wreg + off) = d;
                     }
                 }
             }
@@ -698,9 +714,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 // bias-gradient partial: the band holds the rounded dpre values the weight gradient
                 // will read; rows past the segment and columns past N are exact zeros
 #pragma unroll 8
-                for (int row = 0; row < 32; ++row) {
+                for (int row = 0; row < BAND; ++row) {
                     const uint32_t w2 = *reinterpret_cast<const uint32_t*>(
-                        wreg + row * RPB + ((((lane >> 2) ^ (row & 15))) << 4) + (lane & 3) * 4);
+                        wreg + row * RPB + ((((lane >> 2) ^ row)) << 4) + (lane & 3) * 4);
                     float c0, c1;
                     unpack2<F16>(w2, c0, c1);
                     cs0 += c0; cs1 += c1;
@@ -709,16 +725,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
             // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
             constexpr int RPI_O = 1024 / RPB;            // rows per instruction
 #pragma unroll
-            for (int t = 0; t < 32 / RPI_O; ++t) {
+            for (int t = 0; t < BAND / RPI_O; ++t) {
                 const int row = RPI_O * t + lane / CPRO;
-                const int c = (lane % CPRO) ^ (row & (CPRO - 1));
+                const int c = (lane % CPRO) ^ row;       // row < 16 <= CPRO
                 const int col = wcol0 + c * (16 / ESZ);
-                const int trow = wrow0 + i * 32 + row;
+                const int trow = wrow0 + i * BAND + row;
                 const bool ok = trow < mvalid && col < nvalid;
                 const size_t oi = (size_t)(m0 + trow) * ldo + (size_t)(n0 + col);
                 const u32x4 d0 = *reinterpret_cast<const u32x4*>(wreg + t * 1024 + lane * 16);
                 if constexpr (OP == OP_FC1) {
-                    const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + 8192 + t * 1024 + lane * 16);
+                    const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + H_OFF + t * 1024 + lane * 16);
                     if (ok) {
                         STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
                         STORE16(reinterpret_cast<bf16_t*>(g.out1) + oi, d1);
