@@ -192,7 +192,7 @@ HEXA_API void hexa_moe_profile_enable(int on);
 HEXA_API int hexa_moe_profile_read(int i, const char **label, float *ms_total, int *launches);
 
 /* Benchmark helper (not part of the layer): enqueues a register-only bf16 MFMA loop, `workgroups`
- * workgroups of four wavefronts, each wavefront issuing iters * 16 32x32x16 MFMAs, and writes the FLOP
+ * workgroups of four wavefronts, each wavefront issuing iters * 32 16x16x32 MFMAs, and writes the FLOP
  * count of the launch to *flop (host).  Timed by the caller on `stream`, it gives the matrix rate the
  * part sustains under its power limit.  sink: dev, >= 4 bytes, never written in practice. */
 HEXA_API hexa_status hexa_moe_mfma_probe(int32_t workgroups, int32_t iters, float *sink, void *stream,
