@@ -38,7 +38,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int BK = 64;            // contraction elements per block of the K loop (one 128-byte line per row)
 constexpr int NSLOT = 5;          // LDS ring: five slots, each holds one operand's share of a block
 constexpr int kXcds = 8;         // workgroup i is dispatched to XCD i % 8
-constexpr int kGroupM = 8;       // row tiles per L2-sharing group
+constexpr int kGroupM = 4;       // row tiles per L2-sharing group
+constexpr int kSplitBelow = 128; // row GEMMs with fewer groups cut their last ngroups % 8 groups across the XCDs
 
 enum Op { OP_FC1 = 0, OP_FC2, OP_DGRAD2, OP_DGRAD1, OP_WGRAD2, OP_WGRAD1 };
 
@@ -320,13 +321,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         const int tn = ceil_div(g.N, BN);
         int tile_m, tile_n;
         {   // groups of kGroupM row tiles x all column tiles are dealt round-robin to the XCDs, so
-            // the 8 XCDs work on neighbouring row tiles (mostly one expert) at any time
+            // the 8 XCDs work on neighbouring row tiles (mostly one expert) at any time; the last
+            // ngroups % 8 groups are cut in eight instead, every XCD taking an eighth of each, so
+            // that no XCD is a whole group behind the others at the end
             const int per_group = kGroupM * tn;
             const int ngroups = ceil_div(tm_total, kGroupM);
             const int xcd = item % kXcds, loc = item / kXcds;
-            const int group = (loc / per_group) * kXcds + xcd;
-            const int within = loc % per_group;
-            if (group >= ngroups) return;
+            // rounds of eight whole groups; with many groups the last, partial round is dealt whole
+            // as well (an XCD's CUs finish their tiles one tile-time apart either way, and whole
+            // groups keep their L2 locality), with few the balance matters more
+            const int whole = ngroups >= kSplitBelow ? ceil_div(ngroups, kXcds) : ngroups / kXcds;
+            int group, within, share;
+            if (loc < whole * per_group) {
+                group = (loc / per_group) * kXcds + xcd;
+                if (group >= ngroups) return;
+                within = loc % per_group;
+                share = per_group;
+            } else {
+                const int per8 = ceil_div(per_group, kXcds);
+                const int l2 = loc - whole * per_group;
+                group = whole * kXcds + l2 / per8;
+                if (group >= ngroups) return;
+                const int gtiles = min(kGroupM, tm_total - group * kGroupM) * tn;
+                share = ceil_div(gtiles, kXcds);          // this XCD's tiles of the group
+                if (l2 % per8 >= share) return;
+                within = xcd * share + l2 % per8;
+            }
             const int first = group * kGroupM;
             const int gsz = min(kGroupM, tm_total - first);
             if (within >= gsz * tn) return;
@@ -801,6 +821,16 @@ __global__ __launch_bounds__(256) void wgrad_finish(const int32_t* __restrict__ 
 
 constexpr int kNumCUs = 256;
 
+// Work-item slots of a row GEMM with at most tm_max row tiles and tn column tiles (a multiple of 8):
+// per XCD, enough for either way of dealing the last groups (see gemm_tile).
+inline int row_gemm_slots(int tm_max, int tn) {
+    const int per_group = kGroupM * tn;
+    const int ngroups = ceil_div(tm_max, kGroupM);
+    const int split = (ngroups / kXcds) * per_group + (kXcds - 1) * ceil_div(per_group, kXcds);
+    const int whole = ceil_div(ngroups, kXcds) * per_group;
+    return kXcds * (split > whole ? split : whole);
+}
+
 template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, bool F16 = false>
 void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char* label) {
     ProfScope ps(st, label);
@@ -813,7 +843,7 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char
         attr_done = true;
     }
     const int tm_max = D.A / BM + D.E;
-    const int grid = kXcds * ceil_div(ceil_div(tm_max, kGroupM), kXcds) * kGroupM * ceil_div(g.N, BN);
+    const int grid = row_gemm_slots(tm_max, ceil_div(g.N, BN));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
 }
 
@@ -831,7 +861,7 @@ void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipSt
         attr_done = true;
     }
     const int tm_max = D.A / BM + D.E;
-    const int items_a = kXcds * ceil_div(ceil_div(tm_max, kGroupM), kXcds) * kGroupM * ceil_div(ga.N, BN);
+    const int items_a = row_gemm_slots(tm_max, ceil_div(ga.N, BN));
     const int tmn = ceil_div(gb.M, BM) * ceil_div(gb.N, BN);
     const int items_b = kXcds * ceil_div(tmn, kXcds) * (D.A / gb.chunk_len + D.E);
     {
