@@ -436,6 +436,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #define LOAD_A(kt_, i_) SA::load(ra, (kt_) * a_step, a_row, lna, i_)
 #define LOAD_B(kt_, i_) SB::load(rb, (kt_) * b_step, b_row, lnb, i_)
 
+    // The bias values this lane adds in the epilogue (block j: columns j*16 + 4*grp + 0..3 of the
+    // wave tile), fetched before the K loop: loaded in the epilogue they would be re-read after every
+    // band's stores (which may alias them as far as the compiler knows), each time with the full
+    // memory latency and nothing to hide it behind.  These plain loads are older than every staging
+    // request, so the staging waits, which count from the youngest request back, cover them.
+    u32x2 biasv[FN];
+    if constexpr (OP == OP_FC1 || OP == OP_FC2) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int gc = min(n0 + wn * TN + j * 16 + 4 * grp, g.N - 4);   // masked columns read a valid bias
+            biasv[j] = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
+        }
+    }
+
     f32x4 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -693,8 +707,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 const int col = j * 16 + 4 * grp;                  // column inside the wave tile
                 f32x4 v = acc[i][j];
                 if constexpr (OP == OP_FC1 || OP == OP_FC2) {
-                    const int gc = min(n0 + wcol0 + col, g.N - 4);   // masked columns read a valid bias
-                    const u32x2 bb = *reinterpret_cast<const u32x2*>(g.bias + (size_t)e * g.N + gc);
+                    const u32x2 bb = biasv[j];
                     float b0, b1, b2, b3;
                     unpack2<F16>(bb.x, b0, b1); unpack2<F16>(bb.y, b2, b3);
                     v[0] += b0; v[1] += b1; v[2] += b2; v[3] += b3;
