@@ -33,7 +33,7 @@ METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
 GEMM_LABELS = {"fc1": 1, "fc2": 1, "bwd_fc2": 2, "bwd_fc1": 2}
 # HBM-side bytes per launch at C5 from rocprofv3 (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 after calibration
 # with a plain 1 GiB copy; profiles/c5_gemm_pmc_counters.md).  Only meaningful for --workload C5.
-TRAFFIC_BYTES = {"fc1": 23.7e9, "fc2": 16.0e9, "bwd_fc2": 41.8e9, "bwd_fc1": 35.6e9}
+TRAFFIC_BYTES = {"fc1": 23.5e9, "fc2": 15.8e9, "bwd_fc2": 41.2e9, "bwd_fc1": 34.2e9}
 
 
 def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
