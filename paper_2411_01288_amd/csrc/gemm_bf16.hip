@@ -497,9 +497,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define TR_READ(p_) __builtin_bit_cast(s16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p_)))
 #define TR_JOIN(lo_, p_) __builtin_bit_cast(bf16x8, __builtin_shufflevector((lo_), TR_READ(p_), 0, 1, 2, 3, 4, 5, 6, 7))
-    // The MFMAs of a substep run A-fragment-major (MFMA m = A fragment m / FN x B fragment m % FN),
-    // so the next substep needs A fragment 0 and every B fragment first: its LDS reads are numbered
-    // A0, B0 .. B(FN-1), A1 .. A(FM-1); a K-strided fragment takes two reads (k-rows +0..3 and
+    // The MFMAs of a substep run B-fragment-major (MFMA m = A fragment m % FM x B fragment m / FM),
+    // so the next substep needs B fragment 0 and every A fragment first: its LDS reads are numbered
+    // B0, A0 .. A(FM-1), B1 .. B(FN-1); a K-strided fragment takes two reads (k-rows +0..3 and
     // +4..7), a K-contiguous one takes one.
     constexpr int RA = TOKENS ? 2 : 1, RBn = B_KS ? 2 : 1;
     constexpr int NRD = FM * RA + FN * RBn;
@@ -527,9 +527,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // read number r_ of k-substep s_ from the slots at ab_ (A image) and bb_ (B image)
 #define READ_ONE(fa, fb, ab_, bb_, s_, r_)                                                       \
     do {                                                                                         \
-        if ((r_) < RA) READ_A(fa, ab_, s_, 0, (r_));                                             \
-        else if ((r_) < RA + FN * RBn) READ_B(fb, bb_, s_, ((r_) - RA) / RBn, ((r_) - RA) % RBn); \
-        else if ((r_) < NRD) READ_A(fa, ab_, s_, 1 + ((r_) - RA - FN * RBn) / RA, ((r_) - RA - FN * RBn) % RA); \
+        if ((r_) < RBn) READ_B(fb, bb_, s_, 0, (r_));                                            \
+        else if ((r_) < RBn + FM * RA) READ_A(fa, ab_, s_, ((r_) - RBn) / RA, ((r_) - RBn) % RA); \
+        else if ((r_) < NRD) READ_B(fb, bb_, s_, 1 + ((r_) - RBn - FM * RA) / RBn, ((r_) - RBn - FM * RA) % RBn); \
     } while (0)
 
     constexpr int NM = FM * FN;   // MFMAs per k-substep and wave
@@ -568,10 +568,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         _Pragma("unroll") for (int m = 0; m < NM; ++m) {                                         \
             if constexpr (F16)                                                                   \
                 asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0"                            \
-                             : "+a"(acc[m / FN][m % FN]) : "v"(fb[m % FN]), "v"(fa[m / FN]));    \
+                             : "+a"(acc[m % FM][m / FM]) : "v"(fb[m / FM]), "v"(fa[m % FM]));    \
             else                                                                                 \
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                           \
-                             : "+a"(acc[m / FN][m % FN]) : "v"(fb[m % FN]), "v"(fa[m / FN]));    \
+                             : "+a"(acc[m % FM][m / FM]) : "v"(fb[m / FM]), "v"(fa[m % FM]));    \
             FENCE();                                                                             \
             _Pragma("unroll") for (int r = 0; r < NRD; ++r)                                      \
                 if ((RSPAN * r) / NRD == m) { READ_; }                                           \
