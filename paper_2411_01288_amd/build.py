@@ -17,7 +17,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
 
 # The contraction kernels count their own direct-to-LDS loads in vmcnt; a register spill inside
 # their K loop would add vector-memory operations the count does not know about.  So the build
-# refuses a gemm_bf16.hip whose kernels use any scratch memory at all.
+# refuses a gemm_bf16.hip whose kernels use any scratch memory at all.  (About 1 KB of scratch per
+# lane in one instantiation means its K loop was left rolled: LLVM ignores "#pragma unroll" past a
+# size threshold, -mllvm -pragma-unroll-threshold=N, and the accumulator and fragment arrays are
+# then indexed dynamically and live in scratch.)
 NO_SCRATCH = {"gemm_bf16.hip"}
 
 
