@@ -110,3 +110,15 @@ def test_heterogeneous_allocation(B):
     for bad in (([1.0, 0.0], 10, 1), ([1.0, -2.0], 10, 1), ([1.0], 10, 3), ([], 10, 1), ([1.0], -1, 1)):
         with pytest.raises(B.HexaError):
             B.allocate(*bad)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measured path is one GPU's share; bench.py says so instead of running N > 1."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in (r.stdout + r.stderr)
