@@ -1,5 +1,7 @@
 """Helpers shared by the GPU parity tests: run the HIP library through its binding and
 bring results to the host.  Nothing here computes any part of the layer."""
+import os
+
 import numpy as np
 import torch
 
@@ -33,7 +35,12 @@ def nrm_err(got, ref):
     """max |got - ref| / max |ref|  (the max-abs normalised error of the tolerance statement)."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
-    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+    err = float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+    log = os.environ.get("HEXA_ERR_LOG")      # optional: one line per comparison, for the error survey in the design notes
+    if log:
+        with open(log, "a") as f:
+            f.write(f"{err:.3e}\t{os.environ.get('PYTEST_CURRENT_TEST', '')}\n")
+    return err
 
 
 # fp32 and bf16: the tolerances of the benchmark statement.  fp16 (11-bit significands against bf16's
