@@ -82,3 +82,9 @@ def test_c5_shape_under_zipf_skew_sampled(oracle):
     """The largest shape with C3's Zipf(1.2) routing: one expert holds a large share of the rows,
     which exercises the split token contraction and its fixed-order reduction at full size."""
     sampled_parity(oracle, workload("C5", routing="zipf"), n_tokens=96, n_cols=8)
+
+
+def test_c5_fp16_sampled(oracle):
+    """The largest shape through the fp16 instantiation of the contraction kernels (same launch
+    configuration; tolerance an eighth of bf16's)."""
+    sampled_parity(oracle, workload("C5", dtype="f16"), n_tokens=96, n_cols=8)
