@@ -34,6 +34,8 @@ EXTREMES = [
     (20000, 64, 64, 2, 2, "topk", 503),       # long segments, several weight-gradient chunks, tiny features
     (257, 1024, 64, 3, 1, "topk", 504),       # d >> f
     (257, 64, 1536, 3, 1, "topk", 505),       # f >> d
+    (500, 128, 192, 8, 8, "topk", 506),       # top-8 of 8 (the paper's largest k): every token visits every expert
+    (1200, 64, 128, 32, 8, "zipf", 507),      # top-8 of 32 under skew
 ]
 
 
