@@ -20,12 +20,26 @@
  *     W2, b2, y, dY, dx.  gate and dgate are float.  Weight and bias gradients
  *     are float (the accumulation type).  Index tensors are int32.
  *   - Outputs are overwritten, never accumulated into.
- *   - Errors are return codes; argument checks run on the host before any
- *     launch, so a non-OK return means nothing was enqueued.
- *   - HEXA_BF16 and HEXA_F16 (the MFMA paths) need d % 64 == 0 and f % 64 == 0 (the paper's kernels likewise
- *     assume feature sizes divisible by the tile, App. B), T*d*2 < 2^32 and
- *     d*f*2 < 2^32 (32-bit byte offsets inside x and inside one expert's weight
- *     matrix); HEXA_F32 takes any positive sizes.  E <= 1024.
+ *   - Errors are return codes.  Argument checks run on the host before any
+ *     launch: HEXA_ERR_NULL, _SHAPE, _UNSUPPORTED and _WORKSPACE mean that nothing
+ *     was enqueued.  HEXA_ERR_DEVICE reports a failed launch or set-up call
+ *     (hipGetLastError); launches of the same call that preceded it may already
+ *     be queued, and the outputs are then undefined.
+ *   - Alignment: every tensor pointer must be 16-byte aligned (the kernels use
+ *     16-byte vector accesses), else HEXA_ERR_UNSUPPORTED; the workspace base
+ *     must be 256-byte aligned, else HEXA_ERR_WORKSPACE.
+ *   - HEXA_BF16 and HEXA_F16 (the MFMA paths) need d % 64 == 0 and f % 64 == 0
+ *     (the K loop of the contraction kernels runs in blocks of 64, one 128-byte
+ *     line per operand row; the paper's kernels likewise assume feature sizes
+ *     divisible by the tile, App. B), T*d*2 < 2^32, d*f*2 < 2^32 and
+ *     256*max(d,f)*2 < 2^32 (32-bit byte offsets inside x, inside one expert's
+ *     weight matrix and inside one 256-row tile of an activation matrix);
+ *     HEXA_F32 takes any positive sizes.  E <= 1024.
+ *   - The first hexa_moe_workspace_bytes, hexa_moe_fwd or hexa_moe_bwd call for a
+ *     16-bit shape on a device raises the shared-memory limit of the contraction
+ *     kernels there (once per device, thread-safe).  That set-up call must not
+ *     fall inside a stream capture; sizing the workspace on the device before
+ *     capturing takes care of it.
  *   - Expert ids must satisfy 0 <= topk_idx < E (App. B Table 4).  An id outside
  *     that range is not an error return (the host cannot see it): that
  *     assignment is dropped from the index (inv = -1, offsets[E] < A), it
@@ -48,9 +62,10 @@ typedef enum {
     HEXA_OK = 0,
     HEXA_ERR_NULL = 1,        /* a required pointer is NULL */
     HEXA_ERR_SHAPE = 2,       /* a size is <= 0, A overflows int32, or E > 1024 */
-    HEXA_ERR_UNSUPPORTED = 3, /* dtype or activation unknown, or a bf16 size rule (see above) is not met */
-    HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query */
-    HEXA_ERR_DEVICE = 5       /* a launch failed (hipGetLastError) */
+    HEXA_ERR_UNSUPPORTED = 3, /* dtype or activation unknown, a 16-bit size rule (see above) is not met,
+                                 or a tensor pointer is not 16-byte aligned */
+    HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query, or its base misaligned */
+    HEXA_ERR_DEVICE = 5       /* a launch or a set-up call failed (hipGetLastError) */
 } hexa_status;
 
 typedef enum { HEXA_F32 = 0, HEXA_BF16 = 1, HEXA_F16 = 2 } hexa_dtype;
@@ -158,7 +173,9 @@ HEXA_API hexa_status hexa_moe_bwd(const hexa_moe_shape *shape, const void *dY, c
  * {R_j(x)} as given (Sec. 3.1; App. B Table 5); this entry point produces it from router logits:
  * per token the k largest of E logits, equal logits to the lower expert id, slot j = the j-th
  * largest; gate weights per gate_mode.  Its outputs are what hexa_moe_index / fwd / bwd take.
- *   logits   [T,E] float  dev, in   (finite; a NaN is treated as -inf and makes that row's gates NaN)
+ *   logits   [T,E] float  dev, in   (a NaN counts as -inf: it is selected only after every other
+ *                                    logit of its row and then gets gate 0; a row whose largest
+ *                                    logit is -inf or NaN gets NaN gates)
  *   topk_idx [T,k] int32  dev, out  bit-exact (comparisons only)
  *   gate     [T,k] float  dev, out
  * shape: T, E, k are used (d_model, d_ff, dtype ignored).  k <= min(E, 64), E <= 1024, else
@@ -181,22 +198,6 @@ HEXA_API hexa_status hexa_moe_route(const hexa_moe_shape *shape, const float *lo
  *   latency [n] host, in;  share [n] host, out.  Returns HEXA_ERR_NULL / HEXA_ERR_SHAPE on bad input. */
 HEXA_API hexa_status hexa_moe_allocate(int32_t n, const double *latency, int64_t total, int64_t granule,
                               int64_t *share);
-
-/* Per-kernel timing for benchmarks (not part of the layer).  While enabled, every kernel the
- * library launches is bracketed by two HIP events on its stream; enabling (or disabling)
- * discards earlier records.  This is the only part of the library that creates HIP objects.
- * hexa_moe_profile_read(i, ...) waits for the recorded events and returns the i-th distinct
- * kernel label with its summed duration in ms and its launch count; returns 0 once i is past
- * the last label (or on a HIP error), else 1.  Not thread-safe. */
-HEXA_API void hexa_moe_profile_enable(int on);
-HEXA_API int hexa_moe_profile_read(int i, const char **label, float *ms_total, int *launches);
-
-/* Benchmark helper (not part of the layer): enqueues a register-only bf16 MFMA loop, `workgroups`
- * workgroups of four wavefronts, each wavefront issuing iters * 32 16x16x32 MFMAs, and writes the FLOP
- * count of the launch to *flop (host).  Timed by the caller on `stream`, it gives the matrix rate the
- * part sustains under its power limit.  sink: dev, >= 4 bytes, never written in practice. */
-HEXA_API hexa_status hexa_moe_mfma_probe(int32_t workgroups, int32_t iters, float *sink, void *stream,
-                                double *flop);
 
 #ifdef __cplusplus
 }

@@ -1,6 +1,7 @@
 """Thin Python binding of libhexa_moe (argument marshalling only).
 
-Same names as the C ABI in include/hexa_moe.h.  PyTorch supplies device memory
+Same names as the C ABI in include/hexa_moe.h (and the measurement helpers of
+include/hexa_moe_bench.h).  PyTorch supplies device memory
 and the current stream; every step of the layer runs in the library's kernels.
 Importing this module fails loudly when the library has not been built
 (`python -m paper_2411_01288_amd.build`): there is no fallback path.
@@ -52,7 +53,8 @@ def _load():
     lib.hexa_moe_bwd.restype = ctypes.c_int
     lib.hexa_moe_bwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, Idx, P, S, P, P, P, P, P, P, P]
     lib.hexa_moe_mfma_probe.restype = ctypes.c_int
-    lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
+    lib.hexa_moe_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, P, P,
+                                        ctypes.POINTER(ctypes.c_double)]
     lib.hexa_moe_route.restype = ctypes.c_int
     lib.hexa_moe_route.argtypes = [ctypes.POINTER(Shape), P, ctypes.c_int32, P, P, P]
     lib.hexa_moe_padded_capacity.restype = S
@@ -216,11 +218,12 @@ def profile_read() -> Dict[str, Tuple[float, int]]:
     return out
 
 
-def mfma_probe(workgroups: int, iters: int, sink: "torch.Tensor") -> float:
-    """Enqueue the register-only MFMA loop on the current stream; returns its FLOP count."""
+def mfma_probe(workgroups: int, iters: int, sink: "torch.Tensor", variant: int = 0) -> float:
+    """Enqueue the register-only MFMA loop on the current stream; returns its FLOP count.
+    variant 0: 16x16x32 on random operands, 1: on zeros, 2: 32x32x16 on random operands."""
     flop = ctypes.c_double()
-    _check(lib.hexa_moe_mfma_probe(int(workgroups), int(iters), _ptr(sink, (1,), torch.float32, "sink"),
-                                   _stream(), ctypes.byref(flop)))
+    _check(lib.hexa_moe_mfma_probe(int(variant), int(workgroups), int(iters),
+                                   _ptr(sink, (1,), torch.float32, "sink"), _stream(), ctypes.byref(flop)))
     return flop.value
 
 

@@ -9,7 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhexa_moe.so")
-SOURCES = ["api.hip", "index.hip", "elementwise.hip", "f32_path.hip", "gemm_bf16.hip", "probe.hip", "route.hip"]
+SOURCES = ["api.hip", "index.hip", "elementwise.hip", "f32_path.hip", "gemm_bf16.hip", "probe.hip", "route.hip",
+           "bench_support.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

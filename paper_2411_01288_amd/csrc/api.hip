@@ -2,35 +2,17 @@
 // layer (HEXA-MoE App. B Table 5).  See include/hexa_moe.h for the contract.
 #include "common.h"
 
-#include <cstring>
+#include <atomic>
+#include <mutex>
 #include <vector>
-
-namespace {
-
-struct ProfRec { const char* label; hipEvent_t a, b; };
-bool g_prof_on = false;
-std::vector<ProfRec> g_prof;
-
-}  // namespace
-
-void prof_begin(hipStream_t st, const char* label) {
-    if (!g_prof_on) return;
-    ProfRec r{label, nullptr, nullptr};
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-    (void)hipEventRecord(r.a, st);
-    g_prof.push_back(r);
-}
-
-void prof_end(hipStream_t st) {
-    if (!g_prof_on || g_prof.empty()) return;
-    (void)hipEventRecord(g_prof.back().b, st);
-}
 
 namespace {
 
 constexpr int kMaxExperts = 1024;
 
-hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
+}  // namespace
+
+hexa_status hexa_check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (!s) return HEXA_ERR_NULL;
     if (s->T <= 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return HEXA_ERR_SHAPE;
     if (s->E > kMaxExperts) return HEXA_ERR_SHAPE;
@@ -39,16 +21,22 @@ hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (s->activation < HEXA_ACT_GELU_TANH || s->activation > HEXA_ACT_SILU) return HEXA_ERR_UNSUPPORTED;
     if (s->dtype != HEXA_F32) {
         if (s->d_model % 64 != 0 || s->d_ff % 64 != 0) return HEXA_ERR_UNSUPPORTED;
-        // the bf16 kernels address x (gathered rows) and one expert's weight matrix with 32-bit
-        // byte offsets
+        // the 16-bit kernels address x (gathered rows), one expert's weight matrix and the rows of
+        // one 256-row tile of any activation matrix with 32-bit byte offsets
+        const unsigned long long wide = (unsigned long long)(s->d_model > s->d_ff ? s->d_model : s->d_ff);
         if ((unsigned long long)s->T * s->d_model * 2ull > 0xffffffffull ||
-            (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull)
+            (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull ||
+            256ull * wide * 2ull > 0xffffffffull)
             return HEXA_ERR_UNSUPPORTED;
     }
     D->T = s->T; D->d = s->d_model; D->f = s->d_ff; D->E = s->E; D->k = s->k; D->A = s->T * s->k;
     D->act = s->activation;
     return HEXA_OK;
 }
+
+namespace {
+
+hexa_status check_shape(const hexa_moe_shape* s, MoeDims* D) { return hexa_check_shape(s, D); }
 
 // Carve the workspace.  base may be NULL (size query).
 MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
@@ -90,6 +78,31 @@ bool any_null(std::initializer_list<const void*> ps) {
 }
 
 hexa_status dev(hipError_t e) { return e == hipSuccess ? HEXA_OK : HEXA_ERR_DEVICE; }
+
+// The kernels access tensors with 16-byte vectors and carve the workspace in 256-byte steps.
+bool misaligned(std::initializer_list<const void*> ps, uintptr_t a) {
+    for (const void* p : ps)
+        if (p && ((uintptr_t)p & (a - 1)) != 0) return true;
+    return false;
+}
+
+// One-time set-up per device (kernel launch attributes), with that device current.  The size
+// query runs it too, so a caller that sized its workspace on the device has done it before any
+// stream capture begins.
+std::atomic<bool> g_dev_ready[kMaxDevices];
+std::mutex g_dev_mu;
+hipError_t ensure_device_init() {
+    int d = -1;
+    hipError_t e = hipGetDevice(&d);
+    if (e != hipSuccess) return e;
+    if (d < 0 || d >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_dev_ready[d].load(std::memory_order_acquire)) return hipSuccess;
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    if (g_dev_ready[d].load(std::memory_order_relaxed)) return hipSuccess;
+    e = gemm_bf16_device_init();
+    if (e == hipSuccess) g_dev_ready[d].store(true, std::memory_order_release);
+    return e;
+}
 
 }  // namespace
 
@@ -154,36 +167,8 @@ size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape* shape) {
 size_t hexa_moe_workspace_bytes(const hexa_moe_shape* shape) {
     MoeDims D;
     if (check_shape(shape, &D) != HEXA_OK) return 0;
+    if (shape->dtype != HEXA_F32) (void)ensure_device_init();   // no device here: the entry points will report it
     return layout(D, shape->dtype, nullptr).total_bytes;
-}
-
-void hexa_moe_profile_enable(int on) {
-    for (ProfRec& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-    g_prof.clear();
-    g_prof_on = on != 0;
-}
-
-int hexa_moe_profile_read(int i, const char** label, float* ms_total, int* launches) {
-    // distinct labels in first-seen order
-    std::vector<const char*> names;
-    for (const ProfRec& r : g_prof) {
-        bool seen = false;
-        for (const char* n : names) seen = seen || std::strcmp(n, r.label) == 0;
-        if (!seen) names.push_back(r.label);
-    }
-    if (i < 0 || i >= (int)names.size()) return 0;
-    float total = 0.f;
-    int cnt = 0;
-    for (const ProfRec& r : g_prof) {
-        if (std::strcmp(r.label, names[i]) != 0) continue;
-        float ms = 0.f;
-        if (hipEventSynchronize(r.b) != hipSuccess) return 0;
-        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return 0;
-        total += ms;
-        ++cnt;
-    }
-    *label = names[i]; *ms_total = total; *launches = cnt;
-    return 1;
 }
 
 const char* hexa_moe_status_string(hexa_status s) {
@@ -219,9 +204,11 @@ hexa_status hexa_moe_fwd(const hexa_moe_shape* shape, const void* x, const int32
                   workspace}))
         return HEXA_ERR_NULL;
     const MoeWorkspace ws = layout(D, shape->dtype, workspace);
-    if (workspace_bytes < ws.total_bytes) return HEXA_ERR_WORKSPACE;
+    if (workspace_bytes < ws.total_bytes || misaligned({workspace}, 256)) return HEXA_ERR_WORKSPACE;
+    if (misaligned({x, W1, b1, W2, b2, y}, 16)) return HEXA_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
+    if (shape->dtype != HEXA_F32 && (e = ensure_device_init()) != hipSuccess) return dev(e);
     if (shape->dtype == HEXA_F32) {
         e = launch_f32_fwd(D, (const float*)x, (const float*)W1, (const float*)b1, (const float*)W2,
                            (const float*)b2, idx, ws, st);
@@ -249,9 +236,11 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
                   dx, dW1, db1, dW2, db2}))
         return HEXA_ERR_NULL;
     const MoeWorkspace ws = layout(D, shape->dtype, workspace);
-    if (workspace_bytes < ws.total_bytes) return HEXA_ERR_WORKSPACE;
+    if (workspace_bytes < ws.total_bytes || misaligned({workspace}, 256)) return HEXA_ERR_WORKSPACE;
+    if (misaligned({dY, x, W1, W2, dx, dW1, db1, dW2, db2}, 16)) return HEXA_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
+    if (shape->dtype != HEXA_F32 && (e = ensure_device_init()) != hipSuccess) return dev(e);
     if (shape->dtype == HEXA_F32) {
         e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, (const float*)ws.o, idx.perm,
                                        idx.offsets, gate, (float*)ws.dout, dgate, ws.colpart, db2, st);

@@ -100,18 +100,29 @@ __device__ __forceinline__ SegTile seg_tile_find(const int32_t* __restrict__ off
     return s;
 }
 
-// ---- optional per-kernel timing (off unless hexa_moe_profile_enable(1)) ----
+// ---- optional per-kernel timing (off unless hexa_moe_profile_enable(1); bench_support.hip) ----
 // A ProfScope brackets one kernel launch with two HIP events on the launch stream.
 void prof_begin(hipStream_t st, const char* label);
-void prof_end(hipStream_t st);
+void prof_end(hipStream_t st, const char* label);
 struct ProfScope {
     hipStream_t st;
-    ProfScope(hipStream_t s, const char* label) : st(s) { prof_begin(s, label); }
-    ~ProfScope() { prof_end(st); }
+    const char* label;
+    ProfScope(hipStream_t s, const char* l) : st(s), label(l) { prof_begin(s, l); }
+    ~ProfScope() { prof_end(st, label); }
 };
 
 // ---- internal launchers (one per translation unit), all asynchronous on `st` ----
 struct MoeDims { int T, d, f, E, k, A, act; };
+
+// Host-side validation of a shape (sizes, dtype, activation, the size rules of the 16-bit path);
+// fills D on HEXA_OK.  Touches no device.
+hexa_status hexa_check_shape(const hexa_moe_shape* s, MoeDims* D);
+
+constexpr int kMaxDevices = 64;   // per-device state of the library is kept in arrays of this length
+
+// Sets the launch attributes of every contraction kernel (160 KB of dynamic LDS) on the current
+// device.  Called once per device by the entry points, outside any stream capture.
+hipError_t gemm_bf16_device_init();
 
 // saved + staging regions inside the caller's workspace (device pointers)
 struct MoeWorkspace {

@@ -849,12 +849,6 @@ void launch_rows(const MoeDims& D, const GemmArgs& g, hipStream_t st, const char
     ProfScope ps(st, label);
     auto kern = gemm_bf16<BM, BN, WM, WN, OP, ACT, F16>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_done = true;
-    }
     const int tm_max = D.A / BM + D.E;
     const int grid = row_gemm_slots(tm_max, ceil_div(g.N, BN));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
@@ -867,12 +861,6 @@ void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipSt
                  const char* label, const char* label_fin) {
     auto kern = gemm_bf16_pair<BM, BN, WM, WN, OPA, OPB, F16>;
     constexpr int lds = NSLOT * (BM > BN ? BM : BN) * ROWB;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_done = true;
-    }
     const int tm_max = D.A / BM + D.E;
     const int items_a = row_gemm_slots(tm_max, ceil_div(ga.N, BN));
     const int tmn = ceil_div(gb.M, BM) * ceil_div(gb.N, BN);
@@ -891,6 +879,29 @@ void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipSt
 constexpr int TBM = 256, TBN = 256, TWM = 2, TWN = 2;
 
 }  // namespace
+
+// Every contraction kernel needs the whole 160 KB of LDS as dynamic shared memory, which a kernel
+// may only use after its attribute has been raised, once per device.
+template <typename K>
+static hipError_t allow_full_lds(K kern) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, NSLOT * TBM * ROWB);
+}
+template <bool F16>
+static hipError_t device_init_dtype() {
+    hipError_t e = allow_full_lds(gemm_bf16<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_GELU_TANH, F16>);
+    if (e == hipSuccess) e = allow_full_lds(gemm_bf16<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_RELU, F16>);
+    if (e == hipSuccess) e = allow_full_lds(gemm_bf16<TBM, TBN, TWM, TWN, OP_FC1, HEXA_ACT_SILU, F16>);
+    if (e == hipSuccess) e = allow_full_lds(gemm_bf16<TBM, TBN, TWM, TWN, OP_FC2, HEXA_ACT_GELU_TANH, F16>);
+    if (e == hipSuccess) e = allow_full_lds(gemm_bf16_pair<TBM, TBN, TWM, TWN, OP_DGRAD2, OP_WGRAD2, F16>);
+    if (e == hipSuccess) e = allow_full_lds(gemm_bf16_pair<TBM, TBN, TWM, TWN, OP_DGRAD1, OP_WGRAD1, F16>);
+    return e;
+}
+hipError_t gemm_bf16_device_init() {
+    static_assert(TBM == TBN, "one LDS size for all instantiations");
+    const hipError_t e = device_init_dtype<false>();
+    return e != hipSuccess ? e : device_init_dtype<true>();
+}
 
 // Row-tile height and partial rows per tile of the DGRAD2 column-sum partials (for the finisher).
 int gemm_row_tile() { return TBM; }

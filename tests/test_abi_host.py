@@ -19,7 +19,8 @@ def B():
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "hexa_moe.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, n)).read() for n in sorted(os.listdir(inc)) if n.endswith(".h"))
     return sorted(set(re.findall(r"HEXA_API[^;(]*?\b(hexa_moe_\w+)\s*\(", text)))
 
 
@@ -42,6 +43,7 @@ def test_size_queries_and_shape_validation(B):
                 B.make_shape(8, 64, 64, 2000, 1, "bf16"),          # E > 1024
                 B.make_shape(2 ** 30, 64, 64, 4, 4, "bf16"),       # T*k overflows int32
                 B.make_shape(8, 60, 64, 4, 1, "bf16"),             # bf16 needs multiples of 64
+                B.make_shape(8, 64, 1 << 23, 4, 1, "bf16"),        # 256 rows of d_ff exceed 32-bit byte offsets
                 B.Shape(8, 64, 64, 4, 1, 7, 0),                    # unknown dtype
                 B.make_shape(8, 64, 64, 4, 1, "bf16", 3)):         # unknown activation
         assert B.workspace_bytes(bad) == 0 and B.index_scratch_bytes(bad) == 0
@@ -75,8 +77,20 @@ def test_error_codes_without_touching_a_gpu(B):
     assert lib.hexa_moe_route(ctypes.byref(ok), fake, 2, fake, fake, None) == 3
     assert lib.hexa_moe_route(ctypes.byref(B.make_shape(8, 64, 64, 2000, 2, "bf16")), fake, 0, fake, fake, None) == 2
     flop = ctypes.c_double()
-    assert lib.hexa_moe_mfma_probe(0, 10, fake, None, ctypes.byref(flop)) == 2
-    assert lib.hexa_moe_mfma_probe(4, 10, None, None, ctypes.byref(flop)) == 1
+    assert lib.hexa_moe_mfma_probe(0, 0, 10, fake, None, ctypes.byref(flop)) == 2
+    assert lib.hexa_moe_mfma_probe(0, 4, 10, None, None, ctypes.byref(flop)) == 1
+    assert lib.hexa_moe_mfma_probe(3, 4, 10, fake, None, ctypes.byref(flop)) == 3
+    # alignment: a workspace base off the 256-byte grid, a tensor pointer off the 16-byte grid
+    big = 1 << 40
+    odd_ws, odd_x = P(4096 + 64), P(4096 + 8)
+    assert lib.hexa_moe_fwd(ctypes.byref(ok), fake, fake, fake, fake, fake, fake, fake, idx, fake,
+                            odd_ws, big, None) == 4
+    assert lib.hexa_moe_fwd(ctypes.byref(ok), odd_x, fake, fake, fake, fake, fake, fake, idx, fake,
+                            fake, big, None) == 3
+    assert lib.hexa_moe_bwd(ctypes.byref(ok), fake, fake, fake, fake, fake, fake, idx, odd_ws, big, fake,
+                            fake, fake, fake, fake, None, None) == 4
+    assert lib.hexa_moe_bwd(ctypes.byref(ok), fake, fake, fake, fake, fake, fake, idx, fake, big, fake,
+                            odd_x, fake, fake, fake, None, None) == 3
     for code in range(6):
         assert lib.hexa_moe_status_string(code)
     assert b"unknown" in lib.hexa_moe_status_string(99)
@@ -92,21 +106,24 @@ def test_binding_checks_tensor_shapes_on_the_host(B):
     assert ei.value.code == 3
 
 
-def test_heterogeneous_allocation(B):
-    """Eq. 1 / Eq. 2: shares proportional to 1/latency, integral, exact sum."""
-    from fractions import Fraction
-    assert B.allocate([1.0, 1.0, 1.0, 1.0], 128) == [32, 32, 32, 32]
-    assert B.allocate([1.0, 2.0], 90) == [60, 30]                       # twice as fast, twice the batch
-    assert B.allocate([2.0, 1.0, 1.0], 8192, 64) == [1664, 3264, 3264]  # 25.6 / 51.2 / 51.2 granules -> 26 / 51 / 51
-    got = B.allocate([1.0, 1.0, 1.0], 10)
-    assert got == [4, 3, 3]                                             # ties go to the lower device index
-    lat = [0.8, 1.3, 2.9, 1.0, 5.5]
-    for total, g in ((1000, 1), (4096, 64), (40, 8), (0, 1)):
-        s = B.allocate(lat, total, g)
-        assert sum(s) == total and all(v % g == 0 and v >= 0 for v in s)
-        w = [Fraction(1) / Fraction(t) for t in lat]
-        for v, wi in zip(s, w):                                        # within one granule of the ideal share
-            assert abs(Fraction(v) - wi / sum(w) * total) < g
+def test_heterogeneous_allocation_against_the_oracle(B):
+    """hexa_moe_allocate (Sec. 3.4 Eq. 1 / Eq. 2, largest-remainder rounding) against the exact
+    rational oracle: hand cases, seeded random cases, and its error returns."""
+    import numpy as np
+    from oracle.allocate_oracle import allocate as ref
+    hand = [([1.0, 1.0, 1.0, 1.0], 128, 1), ([1.0, 2.0], 90, 1), ([2.0, 1.0, 1.0], 8192, 64),
+            ([1.0, 1.0, 1.0], 10, 1), ([1.0, 1.0, 1.0], 11, 1), ([0.5, 0.25, 1.0], 6, 1),
+            ([4.58, 3.06], 100, 1), ([3.20, 3.18], 100, 1), ([3.28, 9.42], 100, 1),   # Sec. 4 Table 2
+            ([5.0], 77, 7), ([1.0, 4.0], 0, 1)]
+    for lat, total, g in hand:
+        assert B.allocate(lat, total, g) == ref(lat, total, g), (lat, total, g)
+    rng = np.random.default_rng(2024)
+    for _ in range(500):
+        n = int(rng.integers(1, 9))
+        lat = [float(x) for x in rng.uniform(0.1, 20.0, n)]
+        g = int(rng.choice([1, 8, 64]))
+        total = g * int(rng.integers(0, 2000))
+        assert B.allocate(lat, total, g) == ref(lat, total, g), (lat, total, g)
     for bad in (([1.0, 0.0], 10, 1), ([1.0, -2.0], 10, 1), ([1.0], 10, 3), ([], 10, 1), ([1.0], -1, 1)):
         with pytest.raises(B.HexaError):
             B.allocate(*bad)

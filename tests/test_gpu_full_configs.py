@@ -1,8 +1,20 @@
 """GPU parity at the full sizes of the named workloads C3, C4, C5, in the launch configuration
-bench.py times.  The oracle cannot redo these sizes whole, so: the index is compared in full
-(bit-exact); y, dx, dgate on sampled tokens (random ones, every token of the smallest expert,
-a slice of the largest); dW1, db1, dW2, db2 on sampled experts (largest, smallest non-empty,
-one more) x sampled hidden units, all rows.  Empty experts must give exact zeros.
+bench.py times.  The oracle cannot redo these sizes whole, so the comparison is on a sample that
+is stratified over the tiles the contraction kernels cut the problem into:
+
+  index            compared in full, bit for bit;
+  y, dx, dgate     one token out of every 256-row tile of every expert segment (a tile of the
+                   row GEMMs: fc1, fc2 and the two input-gradient contractions), every token of
+                   the smallest segment, the first and last rows of the largest, and random tokens
+                   up to at least 2048 in total; all d_model columns of each;
+  dW1, db1, dW2,   every expert, on hidden units drawn so that each 256-wide block of d_ff holds
+  db2              at least two (64 or more in total): every 256x256 output tile of both
+                   weight-gradient contractions of every expert is compared on some of its entries,
+                   over all of the expert's rows.
+
+All outputs and the workspace start out as NaN (gpu_util.run_hip_layer), so the finiteness sweep
+at the end shows that every element of every output was written; experts without tokens must
+hold exact zeros.
 """
 import numpy as np
 import pytest
@@ -13,8 +25,46 @@ from gpu_util import TOL, host32, nrm_err, run_hip_layer
 
 pytestmark = pytest.mark.gpu
 
+ROW_TILE = 256      # rows of a row-GEMM tile / columns of a weight-gradient tile
+MIN_TOKENS = 2048
+MIN_COLS = 64
 
-def sampled_parity(oracle, w, n_tokens=192, n_cols=12, seed=0):
+
+def stratified_tokens(rng, w, counts, offsets, perm):
+    """Token ids: one per 256-row tile of every segment + smallest segment + ends of the largest
+    + random ones up to MIN_TOKENS."""
+    picks = []
+    for e in range(w.E):
+        b, n = int(offsets[e]), int(counts[e])
+        for r0 in range(0, n, ROW_TILE):
+            p = b + r0 + int(rng.integers(0, min(ROW_TILE, n - r0)))
+            picks.append(perm[p] // w.k)
+    nonempty = np.nonzero(counts)[0]
+    e_small = int(nonempty[np.argmin(counts[nonempty])])
+    e_big = int(np.argmax(counts))
+    seg = lambda e: perm[offsets[e]:offsets[e + 1]] // w.k
+    picks += list(seg(e_small)[:512]) + list(seg(e_big)[:32]) + list(seg(e_big)[-32:])
+    tok = np.unique(np.asarray(picks, dtype=np.int64))
+    order = rng.permutation(w.T)            # random tokens until MIN_TOKENS distinct ones are in
+    at = 0
+    while tok.size < MIN_TOKENS and at < w.T:
+        tok = np.unique(np.concatenate([tok, order[at:at + MIN_TOKENS - tok.size]]))
+        at += MIN_TOKENS
+    return tok.astype(np.int32), e_small, e_big
+
+
+def stratified_cols(rng, f):
+    """Hidden units: at least two out of every 256-wide block of d_ff, MIN_COLS or more in all."""
+    blocks = (f + ROW_TILE - 1) // ROW_TILE
+    per = max(2, -(-MIN_COLS // blocks))
+    cols = []
+    for b in range(blocks):
+        lo, hi = b * ROW_TILE, min(f, (b + 1) * ROW_TILE)
+        cols += list(rng.choice(np.arange(lo, hi), size=min(per, hi - lo), replace=False))
+    return np.sort(np.asarray(cols)).astype(np.int32)
+
+
+def sampled_parity(oracle, w, seed=0):
     dev = torch.device("cuda:0")
     data = generate(w, dev)
     idx, y, g = run_hip_layer(w, data)
@@ -28,13 +78,16 @@ def sampled_parity(oracle, w, n_tokens=192, n_cols=12, seed=0):
 
     c = {k: host32(v) for k, v in data.items() if k != "topk_idx"}
     rng = np.random.default_rng(seed)
-    nonempty = np.nonzero(counts)[0]
-    e_small = nonempty[np.argmin(counts[nonempty])]
-    e_big = int(np.argmax(counts))
-    seg = lambda e: perm[offsets[e]:offsets[e + 1]] // w.k
-    tok = np.unique(np.concatenate([rng.integers(0, w.T, n_tokens), seg(e_small)[:64],
-                                    seg(e_big)[:32], seg(e_big)[-32:]])).astype(np.int32)
+    tok, e_small, e_big = stratified_tokens(rng, w, counts, offsets, perm)
+    assert tok.size >= MIN_TOKENS
+    # every 256-row tile of every segment holds an assignment of a sampled token
+    hit = np.zeros(w.A, bool)
+    hit[(inv.reshape(w.T, w.k)[tok]).ravel()] = True
+    for e in range(w.E):
+        for r0 in range(int(offsets[e]), int(offsets[e + 1]), ROW_TILE):
+            assert hit[r0:min(r0 + ROW_TILE, int(offsets[e + 1]))].any(), (e, r0)
     tol = TOL[w.dtype]
+    print(f"{w.name} {w.routing} {w.dtype}: {tok.size} tokens ...", flush=True)
     y_ref = oracle.fwd(c["x"], ti, c["gate"], c["W1"], c["b1"], c["W2"], c["b2"], tokens=tok)
     dx_ref, dg_ref = oracle.bwd_tokens(c["x"], ti, c["gate"], c["W1"], c["b1"], c["W2"], c["b2"],
                                        c["dY"], tokens=tok)
@@ -42,16 +95,22 @@ def sampled_parity(oracle, w, n_tokens=192, n_cols=12, seed=0):
     errs = {"y": nrm_err(host32(y[tok_t]), y_ref), "dx": nrm_err(host32(g["dx"][tok_t]), dx_ref),
             "dgate": nrm_err(host32(g["dgate"][tok_t]), dg_ref)}
 
-    experts = np.unique([e_big, e_small, int(rng.choice(nonempty))]).astype(np.int32)
-    cols = np.sort(rng.choice(w.d_ff, n_cols, replace=False)).astype(np.int32)
+    experts = np.arange(w.E, dtype=np.int32)
+    cols = stratified_cols(rng, w.d_ff)
+    assert cols.size >= MIN_COLS
+    print(f"{w.name}: {experts.size} experts x {cols.size} hidden units ...", flush=True)
     dW1, db1, dW2, db2 = oracle.bwd_experts(c["x"], ti, c["gate"], c["W1"], c["b1"], c["W2"], c["dY"],
                                             experts=experts, cols=cols)
-    ex_t = torch.from_numpy(experts.astype(np.int64)).to(dev)
     co_t = torch.from_numpy(cols.astype(np.int64)).to(dev)
-    errs["dW1"] = nrm_err(host32(g["dW1"][ex_t][:, :, co_t]), dW1)
-    errs["db1"] = nrm_err(host32(g["db1"][ex_t][:, co_t]), db1)
-    errs["dW2"] = nrm_err(host32(g["dW2"][ex_t][:, co_t, :]), dW2)
-    errs["db2"] = nrm_err(host32(g["db2"][ex_t]), db2)
+    errs["dW1"] = nrm_err(host32(g["dW1"][:, :, co_t]), dW1)
+    errs["db1"] = nrm_err(host32(g["db1"][:, co_t]), db1)
+    errs["dW2"] = nrm_err(host32(g["dW2"][:, co_t, :]), dW2)
+    errs["db2"] = nrm_err(host32(g["db2"]), db2)
+    # the largest and the smallest segment on their own normalisation (a small expert's gradient
+    # must not hide behind a large one's magnitude)
+    for tag, e in (("big", e_big), ("small", e_small)):
+        errs[f"dW1[{tag}]"] = nrm_err(host32(g["dW1"][e][:, co_t]), dW1[e])
+        errs[f"dW2[{tag}]"] = nrm_err(host32(g["dW2"][e][co_t, :]), dW2[e])
     print(w.name, w.routing, "tokens/expert min", int(counts.min()), "max", int(counts.max()),
           {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
@@ -59,6 +118,7 @@ def sampled_parity(oracle, w, n_tokens=192, n_cols=12, seed=0):
     for e in np.nonzero(counts == 0)[0]:
         for n in ("dW1", "db1", "dW2", "db2"):
             assert float(g[n][int(e)].abs().max()) == 0.0, (n, e)
+    # the outputs were NaN before the calls: finite everywhere = every element was written
     for n in ("dx", "dW1", "db1", "dW2", "db2", "dgate"):
         assert bool(torch.isfinite(g[n]).all()), n
     assert bool(torch.isfinite(y.float()).all())
@@ -81,10 +141,10 @@ def test_c5_large_sampled(oracle):
 def test_c5_shape_under_zipf_skew_sampled(oracle):
     """The largest shape with C3's Zipf(1.2) routing: one expert holds a large share of the rows,
     which exercises the split token contraction and its fixed-order reduction at full size."""
-    sampled_parity(oracle, workload("C5", routing="zipf"), n_tokens=96, n_cols=8)
+    sampled_parity(oracle, workload("C5", routing="zipf"))
 
 
 def test_c5_fp16_sampled(oracle):
     """The largest shape through the fp16 instantiation of the contraction kernels (same launch
     configuration; tolerance an eighth of bf16's)."""
-    sampled_parity(oracle, workload("C5", dtype="f16"), n_tokens=96, n_cols=8)
+    sampled_parity(oracle, workload("C5", dtype="f16"))

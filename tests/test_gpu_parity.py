@@ -76,6 +76,22 @@ def test_bf16_small_shapes(oracle, dev, T, d, f, E, k, routing):
     full_parity(oracle, w, generate(w, dev), label=f"bf16 T{T} d{d} f{f} E{E} k{k} {routing}")
 
 
+@pytest.mark.parametrize("T,d,f,E,k,routing", [
+    (70000, 64, 512, 8, 2, "zipf"),       # 140 000 rows = ~550 row tiles = ~138 groups of four
+    (70000, 64, 256, 64, 2, "bias"),      # the same with 64 experts (C5's count): many segment tails
+])
+def test_bf16_many_row_tiles_full(oracle, dev, T, d, f, E, k, routing):
+    """Row GEMMs deal their 256-row tiles to the eight XCDs in groups of four, and once there are
+    128 groups or more (only C5-sized problems otherwise) the last, partial round of groups is
+    dealt whole instead of being cut in eight.  Small feature sizes let the oracle check every
+    element of such a problem."""
+    w = MoEWorkload("many-tiles", T, d, f, E, k, "bf16", routing, 4242 + E)
+    data = generate(w, dev)
+    counts = np.bincount(data["topk_idx"].cpu().numpy().ravel(), minlength=E)
+    assert sum(-(-int(n) // 256) for n in counts) >= 4 * 128
+    full_parity(oracle, w, data, label=f"bf16 T{T} d{d} f{f} E{E} k{k} {routing}")
+
+
 def test_c2_bf16_full(oracle, dev):
     w = workload("C2")
     full_parity(oracle, w, generate(w, dev))

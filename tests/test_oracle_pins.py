@@ -451,3 +451,86 @@ def test_activation_scalar_values(oracle, with_activation):
     assert oracle.act(0.9) == oracle.gelu(0.9) and oracle.act_grad(0.9) == oracle.gelu_grad(0.9)
     with pytest.raises(ValueError):
         oracle.set_activation(7)
+
+
+# ---- heterogeneous-aware allocation (Sec. 3.4 Eq. 1-2) ------------------------------------------
+
+def _alloc_fixture():
+    rows = []
+    for line in open(os.path.join(GOLD, "alloc_table2.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        c, t0, t1, r0, r1 = line.split()
+        rows.append((int(c), float(t0), float(t1), r0, r1))
+    return rows
+
+
+def test_allocation_reproduces_the_paper_capacity_table():
+    """Sec. 4 Table 2 prints, for three power settings of its two GPUs, the measured latencies and
+    the capacity proportion R = Eq. 1 / Eq. 2 with total 1, to two decimals."""
+    from oracle.allocate_oracle import ideal_shares
+    rows = _alloc_fixture()
+    assert len(rows) == 3
+    for _, t0, t1, r0, r1 in rows:
+        q = ideal_shares([t0, t1], 1)
+        assert sum(q) == 1
+        assert f"{float(q[0]):.2f}" == r0 and f"{float(q[1]):.2f}" == r1
+        # and the split of a batch of 100 in whole samples is that proportion
+        from oracle.allocate_oracle import allocate
+        s = allocate([t0, t1], 100)
+        assert s == [round(float(q[0]) * 100), 100 - round(float(q[0]) * 100)]
+
+
+def test_allocation_closed_forms_and_invariants():
+    from fractions import Fraction
+    from oracle.allocate_oracle import allocate, ideal_shares
+    assert allocate([3.0] * 4, 128) == [32] * 4                 # equal devices, equal shares
+    assert allocate([1.0, 2.0], 90) == [60, 30]                 # half the latency, twice the work
+    assert allocate([1.0, 1.0, 1.0], 10) == [4, 3, 3]           # equal fractions: lower index first
+    assert allocate([1.0, 1.0, 1.0], 11) == [4, 4, 3]
+    assert allocate([2.0, 1.0, 1.0], 8192, 64) == [1664, 3264, 3264]   # 25.6 / 51.2 / 51.2 granules
+    assert allocate([5.0], 77, 7) == [77]
+    assert allocate([1.0, 4.0], 0) == [0, 0]
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        n = int(rng.integers(1, 7))
+        lat = [float(x) for x in rng.uniform(0.2, 9.0, n)]
+        g = int(rng.choice([1, 8, 64]))
+        total = g * int(rng.integers(0, 300))
+        s = allocate(lat, total, g)
+        q = ideal_shares(lat, total)
+        assert sum(s) == total and sum(q) == total
+        assert all(v % g == 0 and v >= 0 for v in s)
+        assert all(abs(Fraction(v) - qi) < g for v, qi in zip(s, q))       # within one granule
+        # scaling every latency by the same factor changes nothing (only ratios enter Eq. 1-2)
+        assert allocate([2.0 * t for t in lat], total, g) == s
+        # a faster device never gets less
+        order = np.argsort(lat)
+        assert all(s[order[i]] >= s[order[i + 1]] for i in range(n - 1))
+    for bad in (([1.0, 0.0], 10, 1), ([1.0, -2.0], 10, 1), ([1.0], 10, 3), ([], 10, 1), ([1.0], -1, 1)):
+        with pytest.raises(ValueError):
+            allocate(*bad)
+
+
+def test_allocation_against_brute_force_over_all_splits():
+    """Largest-remainder rounding is the integer split closest to the ideal shares in the L1 sense;
+    among equally close ones the rule hands the extra units to the lower device index, i.e. picks
+    the lexicographically largest.  Enumerate every split of a few units over 2-3 devices."""
+    from fractions import Fraction
+    from itertools import product
+    from oracle.allocate_oracle import allocate, ideal_shares
+    rng = np.random.default_rng(5)
+    cases = [([1.0, 1.0], 5), ([1.0, 1.0, 1.0], 7), ([1.0, 2.0, 4.0], 9), ([0.5, 0.25, 1.0], 6)]
+    for _ in range(40):
+        n = int(rng.integers(2, 4))
+        cases.append(([float(x) for x in rng.integers(1, 9, n)], int(rng.integers(0, 13))))
+    for lat, units in cases:
+        q = ideal_shares(lat, units)
+        best, best_cost = None, None
+        for s in product(range(units + 1), repeat=len(lat)):
+            if sum(s) != units:
+                continue
+            cost = sum(abs(Fraction(v) - qi) for v, qi in zip(s, q))
+            if best is None or cost < best_cost or (cost == best_cost and s > best):
+                best, best_cost = s, cost
+        assert tuple(allocate(lat, units)) == best, (lat, units)
