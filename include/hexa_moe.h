@@ -64,7 +64,8 @@ typedef enum {
     HEXA_ERR_SHAPE = 2,       /* a size is <= 0, A overflows int32, or E > 1024 */
     HEXA_ERR_UNSUPPORTED = 3, /* dtype or activation unknown, a 16-bit size rule (see above) is not met,
                                  or a tensor pointer is not 16-byte aligned */
-    HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query, or its base misaligned */
+    HEXA_ERR_WORKSPACE = 4,   /* scratch / workspace smaller than the *_bytes() query, its base misaligned,
+                                 or (hexa_moe_index_static) the shape needs more than the built-in scratch */
     HEXA_ERR_DEVICE = 5       /* a launch or a set-up call failed (hipGetLastError) */
 } hexa_status;
 
@@ -114,6 +115,23 @@ HEXA_API const char *hexa_moe_status_string(hexa_status s);
 HEXA_API hexa_status hexa_moe_index(const hexa_moe_shape *shape, const int32_t *topk_idx,
                            hexa_moe_idx out, void *scratch, size_t scratch_bytes,
                            void *stream);
+
+/* hexa_moe_index for callers that cannot allocate device memory (code under HIP stream capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same inputs, same outputs, same kernels,
+ * but the chunk-histogram scratch is a fixed array of HEXA_INDEX_STATIC_SCRATCH_BYTES that the
+ * library holds in each GPU's memory from load until the process ends.  The call allocates and
+ * frees nothing and takes no scratch argument.
+ *   - Limit: hexa_moe_index_scratch_bytes(shape) <= HEXA_INDEX_STATIC_SCRATCH_BYTES, else
+ *     HEXA_ERR_WORKSPACE with nothing enqueued.  1 MiB covers min(ceil(T*k/64), 1024) * E <= 262 144:
+ *     any T*k when E <= 256, any E <= 1024 when T*k <= 16 384.
+ *   - The first call on a device looks the array's address up there (one host call, no stream
+ *     work; make it outside a capture) and returns HEXA_ERR_DEVICE if that fails.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap on one GPU
+ *     (different streams, or different host threads on different streams) race.  Calls on one
+ *     stream are ordered and safe; nothing needs clearing between calls. */
+#define HEXA_INDEX_STATIC_SCRATCH_BYTES (1u << 20)
+HEXA_API hexa_status hexa_moe_index_static(const hexa_moe_shape *shape, const int32_t *topk_idx,
+                                  hexa_moe_idx out, void *stream);
 
 /* The paper's own form of the index (App. B Alg. 1; Sec. 3.2), derived from hexa_moe_index's output
  * for callers written against it: every expert's sub-vector padded with -1 up to a multiple of the

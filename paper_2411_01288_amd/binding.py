@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
 
 HEXA_F32, HEXA_BF16, HEXA_F16 = 0, 1, 2
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",
-           "hexa_moe_index", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
+           "hexa_moe_index", "hexa_moe_index_static", "hexa_moe_fwd", "hexa_moe_bwd", "hexa_moe_profile_enable",
            "hexa_moe_profile_read", "hexa_moe_mfma_probe", "hexa_moe_route",
            "hexa_moe_allocate", "hexa_moe_padded_capacity", "hexa_moe_padded_index")
 
@@ -48,6 +48,8 @@ def _load():
     lib.hexa_moe_status_string.argtypes = [ctypes.c_int]
     lib.hexa_moe_index.restype = ctypes.c_int
     lib.hexa_moe_index.argtypes = [ctypes.POINTER(Shape), P, Idx, P, S, P]
+    lib.hexa_moe_index_static.restype = ctypes.c_int
+    lib.hexa_moe_index_static.argtypes = [ctypes.POINTER(Shape), P, Idx, P]
     lib.hexa_moe_fwd.restype = ctypes.c_int
     lib.hexa_moe_fwd.argtypes = [ctypes.POINTER(Shape), P, P, P, P, P, P, P, Idx, P, P, S, P]
     lib.hexa_moe_bwd.restype = ctypes.c_int
@@ -157,6 +159,17 @@ def hexa_moe_index(shape: Shape, topk_idx: torch.Tensor, idx: Optional[Dict[str,
                               _ptr(topk_idx, (shape.T, shape.k), torch.int32, "topk_idx"),
                               _idx_struct(shape, idx), ctypes.c_void_p(scratch.data_ptr()),
                               scratch.numel(), _stream()))
+    return idx
+
+
+INDEX_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def hexa_moe_index_static(shape: Shape, topk_idx: torch.Tensor, idx: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:
+    """hexa_moe_index without a scratch argument and without any allocation: `idx` must be given."""
+    _check(lib.hexa_moe_index_static(ctypes.byref(shape),
+                                     _ptr(topk_idx, (shape.T, shape.k), torch.int32, "topk_idx"),
+                                     _idx_struct(shape, idx), _stream()))
     return idx
 
 

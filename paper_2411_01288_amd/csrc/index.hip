@@ -16,6 +16,8 @@
 // Segments carry no padding: tiles are cut per segment by the consumers.
 #include "common.h"
 
+#include <mutex>
+
 namespace {
 
 constexpr int kWavesPerWg = 4;
@@ -232,4 +234,52 @@ hipError_t launch_index(const MoeDims& D, const int32_t* topk_idx, hexa_moe_idx 
     hipLaunchKernelGGL(index_scatter, dim3(nwg), dim3(256), lds, st, topk_idx, D.A, D.E,
                        p.rows_per_wave, p.nchunks, hist, out.offsets, out.perm, out.inv); }
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// hexa_moe_index_static: the same three kernels with the chunk histogram in a fixed array of
+// device memory that belongs to the library, for callers that cannot allocate (no hipMalloc under
+// stream capture, tight serving loops).  Nothing here allocates or frees.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+// One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[HEXA_INDEX_STATIC_SCRATCH_BYTES];
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up on first use
+
+// The address of this device's copy of the array (the device must be current).
+hipError_t static_scratch(void** out) {
+    int d = -1;
+    hipError_t e = hipGetDevice(&d);
+    if (e != hipSuccess) return e;
+    if (d < 0 || d >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[d]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[d] = p;
+    }
+    *out = g_scratch_ptr[d];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" hexa_status hexa_moe_index_static(const hexa_moe_shape* shape, const int32_t* topk_idx,
+                                             hexa_moe_idx out, void* stream) {
+    MoeDims D;
+    const hexa_status s = hexa_check_shape(shape, &D);
+    if (s != HEXA_OK) return s;
+    if (!topk_idx || !out.counts || !out.offsets || !out.perm || !out.inv) return HEXA_ERR_NULL;
+    if (index_scratch_bytes(D) > (size_t)HEXA_INDEX_STATIC_SCRATCH_BYTES) return HEXA_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    if (static_scratch(&ptr) != hipSuccess) return HEXA_ERR_DEVICE;
+    // index_count overwrites every histogram entry the later kernels read, so what an earlier
+    // call left in the array needs no clearing
+    return launch_index(D, topk_idx, out, ptr, (hipStream_t)stream) == hipSuccess ? HEXA_OK : HEXA_ERR_DEVICE;
 }

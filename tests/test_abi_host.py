@@ -69,6 +69,13 @@ def test_error_codes_without_touching_a_gpu(B):
                             fake, fake, fake, fake, None, None) == 4
     assert lib.hexa_moe_fwd(ctypes.byref(ok), None, fake, fake, fake, fake, fake, fake, idx, fake,
                             fake, 1 << 40, None) == 1
+    # the allocation-free index: same checks, and a shape beyond its built-in scratch is refused
+    assert lib.hexa_moe_index_static(None, fake, idx, None) == 1
+    assert lib.hexa_moe_index_static(ctypes.byref(ok), None, idx, None) == 1
+    assert lib.hexa_moe_index_static(ctypes.byref(bad), fake, idx, None) == 3
+    wide = B.make_shape(100000, 64, 64, 1024, 3, "bf16")
+    assert B.index_scratch_bytes(wide) > B.INDEX_STATIC_SCRATCH_BYTES
+    assert lib.hexa_moe_index_static(ctypes.byref(wide), fake, idx, None) == 4
     # router front-end: k > E and k > 64 are unsupported, E > 1024 is a shape error
     assert lib.hexa_moe_route(None, fake, 0, fake, fake, None) == 1
     assert lib.hexa_moe_route(ctypes.byref(ok), None, 0, fake, fake, None) == 1
