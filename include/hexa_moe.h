@@ -104,7 +104,8 @@ HEXA_API size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape *shape);
  * per-assignment expert outputs, in perm order) plus backward staging.  256-byte alignment of the base is required. */
 HEXA_API size_t hexa_moe_workspace_bytes(const hexa_moe_shape *shape);
 
-HEXA_API const char *hexa_moe_status_string(hexa_status s);
+/* Text for a status code; any other integer gives "unknown status" (hence int, not the enum). */
+HEXA_API const char *hexa_moe_status_string(int status);
 
 /* Re-index build (App. B Alg. 1; Sec. 3.2 "Re-Index based Expert-Specific
  * Operators"), for all k routing slots at once.

@@ -20,12 +20,20 @@ _P = ctypes.c_void_p
 _I = ctypes.c_int
 
 
+# HEXA_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (the process must then run with the ASan runtime preloaded; see
+# tests/test_sanitizers.py).
+_SAN = os.environ.get("HEXA_ORACLE_SANITIZE") == "1"
+if _SAN:
+    _LIB = os.path.join(_HERE, "libhexa_oracle_asan.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with g++ (-O3, OpenMP over disjoint outputs only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["g++", "-O3", "-march=native", "-fopenmp", "-shared", "-fPIC", "-Wall",
-             "-o", _LIB, _SRC])
+        opt = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                "-fno-sanitize-recover=undefined"] if _SAN else ["-O3", "-march=native"])
+        subprocess.check_call(["g++", *opt, "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC])
     return _LIB
 
 

@@ -15,7 +15,9 @@ from typing import Dict, Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhexa_moe.so")
+# HEXA_MOE_SANITIZE=1 loads the host-sanitizer build instead (build.py --sanitize; CPU-side tests only)
+LIB_PATH = os.path.join(_HERE, "libhexa_moe_asan.so" if os.environ.get("HEXA_MOE_SANITIZE") == "1"
+                        else "libhexa_moe.so")
 
 HEXA_F32, HEXA_BF16, HEXA_F16 = 0, 1, 2
 EXPORTS = ("hexa_moe_index_scratch_bytes", "hexa_moe_workspace_bytes", "hexa_moe_status_string",

@@ -55,5 +55,37 @@ def build_library(jobs: int = 7) -> str:
     return LIB
 
 
+# ---- host-code sanitizer build (CPU-side checks only; the device code is compiled as usual) ----
+SAN_LIB = os.path.join(HERE, "libhexa_moe_asan.so")
+SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+            "-Xarch_host", "-fno-sanitize-recover=undefined"]
+
+
+def sanitizer_runtime() -> str:
+    """Path of the AddressSanitizer runtime that the sanitized library needs preloaded."""
+    out = subprocess.check_output(["/opt/rocm/llvm/bin/clang++", "-print-file-name=libclang_rt.asan-x86_64.so"],
+                                  text=True).strip()
+    if not os.path.exists(out):
+        raise RuntimeError("clang's AddressSanitizer runtime was not found")
+    return out
+
+
+def build_sanitized_library(jobs: int = 7) -> str:
+    """libhexa_moe_asan.so: the same sources with AddressSanitizer and UndefinedBehaviorSanitizer on the
+    host code (argument checks, workspace layout, launch set-up).  tests/test_sanitizers.py runs the
+    host-only ABI tests against it; GPU sanitizers are not used."""
+    def one(src: str) -> str:
+        obj = os.path.join(CSRC, src.replace(".hip", ".asan.o"))
+        flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g", "-fno-omit-frame-pointer"]
+        subprocess.check_call(["hipcc", *flags, *SAN_HOST, "-c", os.path.join(CSRC, src), "-o", obj])
+        return obj
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(one, SOURCES))
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined",
+                           "-shared-libsan", "-o", SAN_LIB, *objs])
+    return SAN_LIB
+
+
 if __name__ == "__main__":
-    print(build_library())
+    import sys
+    print(build_sanitized_library() if "--sanitize" in sys.argv[1:] else build_library())

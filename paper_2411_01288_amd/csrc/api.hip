@@ -171,13 +171,13 @@ size_t hexa_moe_workspace_bytes(const hexa_moe_shape* shape) {
     return layout(D, shape->dtype, nullptr).total_bytes;
 }
 
-const char* hexa_moe_status_string(hexa_status s) {
+const char* hexa_moe_status_string(int s) {
     switch (s) {
         case HEXA_OK: return "ok";
         case HEXA_ERR_NULL: return "a required pointer is NULL";
         case HEXA_ERR_SHAPE: return "invalid shape";
-        case HEXA_ERR_UNSUPPORTED: return "unsupported dtype or feature size";
-        case HEXA_ERR_WORKSPACE: return "scratch or workspace too small";
+        case HEXA_ERR_UNSUPPORTED: return "unsupported dtype, feature size or pointer alignment";
+        case HEXA_ERR_WORKSPACE: return "scratch or workspace too small or misaligned";
         case HEXA_ERR_DEVICE: return "kernel launch failed";
     }
     return "unknown status";
