@@ -31,9 +31,23 @@ METRIC = "MoE layer fwd+bwd useful TFLOP/s on 1 MI355X + % of bf16 MFMA peak"
 # contraction launches: label -> number of 2*A*d*f contractions in the launch (the backward of each
 # linear layer runs its input-gradient and weight-gradient contractions in one grid)
 GEMM_LABELS = {"fc1": 1, "fc2": 1, "bwd_fc2": 2, "bwd_fc1": 2}
-# HBM-side bytes per launch at C5 from rocprofv3 (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 after calibration
-# with a plain 1 GiB copy; profiles/c5_gemm_pmc_counters.md).  Only meaningful for --workload C5.
-TRAFFIC_BYTES = {"fc1": 23.5e9, "fc2": 15.8e9, "bwd_fc2": 41.2e9, "bwd_fc1": 34.2e9}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "c5_gemm_pmc_counters.md")
+
+
+def profiled_traffic():
+    """HBM-side bytes per launch at C5 from the committed rocprofv3 summary (FETCH_SIZE and WRITE_SIZE,
+    calibrated with a plain 1 GiB copy): {launch label: bytes}.  The counters cannot be read from
+    inside a timed run, so this is the profile's figure, not this run's; {} if the table is missing."""
+    out = {}
+    try:
+        for line in open(TRAFFIC_FILE):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 6 and cells[1].startswith("gemm_bf16") and "(" in cells[1]:
+                label = cells[1].rsplit("(", 1)[1].rstrip(")")
+                out[label] = (float(cells[3]) + float(cells[5])) * 1e9
+    except (OSError, ValueError):
+        return {}
+    return out
 
 
 def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
@@ -50,6 +64,7 @@ def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
     W1, b1, W2, b2 = h(data["W1"]), h(data["b1"]), h(data["W2"]), h(data["b2"])
     ncols = max(1, w.d_ff // col_frac)
     cols = np.arange(ncols, dtype=np.int32)
+    c0 = time.process_time()
     t0 = time.perf_counter()
     O.fwd(x, idx, gate, W1, b1, W2, b2)
     t1 = time.perf_counter()
@@ -57,15 +72,21 @@ def cpu_baseline(w, data, sample_tokens=2048, col_frac=16):
     t2 = time.perf_counter()
     O.bwd_experts(x, idx, gate, W1, b1, W2, dY, cols=cols)
     t3 = time.perf_counter()
+    c1 = time.process_time()
     per_assign = ((t1 - t0) + (t2 - t1) + (t3 - t2) * (w.d_ff / ncols)) / (S * w.k)
     tflops = 12.0 * w.d_model * w.d_ff / per_assign / 1e12
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    # threads the oracle's OpenMP regions ran with: the team size, capped by the CPUs this process
+    # may run on; busy = CPU seconds per wall second over the timed calls (what the box really gave)
+    threads = min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), len(os.sched_getaffinity(0)))
+    busy = (c1 - c0) / max(t3 - t0, 1e-9)
     return {
-        "value": tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "value": tflops, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "cpu_seconds_per_wall_second": round(busy, 2),
         "sample": (f"first {S} tokens ({S * w.k} assignments) of the same batch, all {w.E} experts "
                    f"resident; fwd {t1 - t0:.2f}s + dx/dgate {t2 - t1:.2f}s + weight/bias grads on "
                    f"{ncols}/{w.d_ff} hidden units {t3 - t2:.2f}s (scaled x{w.d_ff // ncols}); "
-                   f"rate = 12*d*f / time per assignment"),
+                   f"rate = 12*d*f / time per assignment; {threads} OpenMP threads on "
+                   f"{len(os.sched_getaffinity(0))} schedulable CPUs, {busy:.1f} of them busy on average"),
     }
 
 
@@ -186,6 +207,14 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     sustained = probe_flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    probes = {"16x16x32_random": round(sustained, 1)}
+    for name, variant in (("16x16x32_zero_operands", 1), ("32x32x16_random", 2)):
+        B.mfma_probe(1024, 2000, sink, variant)
+        e0.record()
+        flop = B.mfma_probe(1024, 30000, sink, variant)
+        e1.record()
+        torch.cuda.synchronize()
+        probes[name] = round(flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
 
     # the router front-end (the step before the path; not part of `value`): HBM-bound,
     # T*E*4 bytes of logits in, T*k*8 bytes out
@@ -238,9 +267,12 @@ def main():
                    "tokens_per_expert": {"min": int(counts.min()), "max": int(counts.max())}},
         "roofline": {"bound": "mfma", "kernel": f"gemm_bf16<{dom}>", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom) if w.name == "C5" and not args.routing else None,
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": profiled_traffic().get(dom) if w.name == "C5" and not args.routing and not args.dtype else None,
+                     "traffic_source": "profiles/c5_gemm_pmc_counters.md (rocprofv3 FETCH_SIZE + WRITE_SIZE per launch; not this run)",
                      "flop_per_launch": gemm_flop, "avg_ms": kernels[dom]["ms"],
-                     "sustained_mfma_peak": sustained, "frac_of_sustained": achieved / sustained},
+                     "sustained_mfma_peak": sustained, "frac_of_sustained": achieved / sustained,
+                     "mfma_probe_tflops": probes},
         # sums of kernel durations per step (HIP events); "fwd_incl_index" = index + fwd
         "phases_ms": {"index": round(idx_ms, 4), "fwd": round(fwd_ms, 4),
                       "fwd_incl_index": round(idx_ms + fwd_ms, 4),

@@ -100,8 +100,9 @@ HEXA_API size_t hexa_moe_index_scratch_bytes(const hexa_moe_shape *shape);
 
 /* Bytes of device workspace shared by hexa_moe_fwd and hexa_moe_bwd (0 on an
  * invalid shape).  It holds what the forward pass saves for the backward pass
- * (pre-activations or the activation's derivative at them, activations and
- * per-assignment expert outputs, in perm order) plus backward staging.  256-byte alignment of the base is required. */
+ * (pre-activations or the activation's derivative at them, activations,
+ * per-assignment expert outputs, in perm order, and the tile lists derived from
+ * the index) plus backward staging.  256-byte alignment of the base is required. */
 HEXA_API size_t hexa_moe_workspace_bytes(const hexa_moe_shape *shape);
 
 /* Text for a status code; any other integer gives "unknown status" (hence int, not the enum). */

@@ -136,7 +136,7 @@ struct MoeWorkspace {
     float* colpart; // [rows, max(d,f)] f32 partial column sums          (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
     size_t kpart_slots;
-    int32_t* worklist; // row tiles and token-contraction items of the bf16 kernels (rebuilt by fwd and bwd)
+    int32_t* worklist; // row tiles and token-contraction items of the bf16 kernels (saved by fwd, read by bwd)
     size_t total_bytes;
 };
 

@@ -246,7 +246,8 @@ __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& til
     tile_n = in / gsz;
 }
 
-// Work lists, built once per forward / backward call from the segment offsets, so that a
+// Work lists, built once per forward call from the segment offsets (the backward pass reads the same
+// lists: they are part of what the forward pass leaves in the workspace), so that a
 // workgroup finds its tile with two scalar loads instead of a walk over all experts (which cost a
 // 256x256 tile of a d = 2048 contraction about a tenth of its time, with the CU idle meanwhile).
 //   wl[0] = number of row tiles, wl[1] = number of token-contraction items, wl[2..3] unused
@@ -962,8 +963,8 @@ static hipError_t bwd_impl(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     GemmArgs g{};
     g.offsets = idx.offsets; g.perm = idx.perm; g.topk = D.k; g.E = D.E;
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
+    // the work lists are the ones the forward pass built (part of the state it saves in the workspace)
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
-    launch_worklists(D, idx, ws, st);
     // 2nd linear layer: dpre = (do W2^T) * F'(pre)  and  dW2[e] = h^T do
     GemmArgs r = g, t = g;
     r.A = (const bf16_t*)ws.dout; r.B = W2; r.pre_in = (const bf16_t*)ws.pre; r.out0 = ws.dpre;
