@@ -32,8 +32,9 @@
  *     (the K loop of the contraction kernels runs in blocks of 64, one 128-byte
  *     line per operand row; the paper's kernels likewise assume feature sizes
  *     divisible by the tile, App. B), T*d*2 < 2^32, d*f*2 < 2^32 and
- *     256*max(d,f)*2 < 2^32 (32-bit byte offsets inside x, inside one expert's
- *     weight matrix and inside one 256-row tile of an activation matrix);
+ *     256*max(d,f)*4 < 2^31 (32-bit byte offsets inside x, inside one expert's
+ *     weight matrix and inside one 256-row tile of an activation or gradient
+ *     matrix);
  *     HEXA_F32 takes any positive sizes.  E <= 1024.
  *   - The first hexa_moe_workspace_bytes, hexa_moe_fwd or hexa_moe_bwd call for a
  *     16-bit shape on a device raises the shared-memory limit of the contraction

@@ -22,11 +22,12 @@ hexa_status hexa_check_shape(const hexa_moe_shape* s, MoeDims* D) {
     if (s->dtype != HEXA_F32) {
         if (s->d_model % 64 != 0 || s->d_ff % 64 != 0) return HEXA_ERR_UNSUPPORTED;
         // the 16-bit kernels address x (gathered rows), one expert's weight matrix and the rows of
-        // one 256-row tile of any activation matrix with 32-bit byte offsets
+        // one 256-row tile of any activation matrix with 32-bit byte offsets; the output window of a
+        // tile (256 rows of fp32 at most) must stay below 2^31 bytes, the offset that masks a lane
         const unsigned long long wide = (unsigned long long)(s->d_model > s->d_ff ? s->d_model : s->d_ff);
         if ((unsigned long long)s->T * s->d_model * 2ull > 0xffffffffull ||
             (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull ||
-            256ull * wide * 2ull > 0xffffffffull)
+            256ull * wide * 4ull > 0x7fffffffull)
             return HEXA_ERR_UNSUPPORTED;
     }
     D->T = s->T; D->d = s->d_model; D->f = s->d_ff; D->E = s->E; D->k = s->k; D->A = s->T * s->k;

@@ -594,8 +594,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // requests B(j+2) into A(j)'s slot while it reads the first fragments of block j+1.  Past the
     // last block the requests re-fetch the last block into slots nobody reads, which keeps the
     // loop body free of branches.
-    const int klast = nk > 0 ? nk - 1 : 0;
-    if (nk > 0) {
+    // nk >= 1: K is at least one block in the row GEMMs, and a token-contraction item holds at least
+    // one row.  The K loop is bottom-tested for that reason: with a zero-trip path the accumulators
+    // of the two paths meet behind the loop, and the register allocator shuffles them there.
+    const int klast = nk - 1;
+    {
         const uint32_t k1 = (uint32_t)min(1, klast);
         _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 0 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(0u, o); }
         _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 1 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(0u, o); }
@@ -607,7 +610,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     _Pragma("unroll") for (int r = 0; r < NRD; ++r) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, r);
 
     int sa = 0, sb = 1;                           // slots of A(j), B(j)
-    for (int j = 0; j < nk; ++j) {
+    int j = 0;
+    do {
         uint8_t* abase = smem + sa * SLOT;
         uint8_t* bbase = smem + sb * SLOT;
         const int sa1 = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
@@ -625,7 +629,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         FENCE();
         SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, r), STAGE_AT(m, PREP_B, LOAD_B, b2, kreq));
         sa = sa1; sb = sb1;
-    }
+    } while (++j < nk);
     // no staging write may still be in flight when the workgroup gives its LDS back
     // (the MFMAs are inline assembly, so the compiler does not count the wait states their results
     // need before the epilogue reads the accumulators: 16 idle cycles cover the 4-pass MFMA)
@@ -658,7 +662,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // 512-byte row segments.  DGRAD2's saved activation derivatives come in the same way, staged
     // one band ahead.
     __syncthreads();   // every wave is done reading fragments
-#define STORE16(p_, v_) (*reinterpret_cast<u32x4*>(p_) = (v_))
     {
         uint8_t* wreg = smem + uwave * 32768;
         constexpr bool OUT_F32 = TOKENS;   // weight gradients; every activation-like output is 16-bit
@@ -691,6 +694,42 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 }
             }
         };
+        // Output window of this wave: a buffer resource from (first row, first column) of the wave
+        // tile to the end of its last valid row, so stores to rows past the segment are dropped by
+        // the range check; a lane whose 16-byte chunk lies past the last valid column gets an
+        // offset outside any window.  Instruction t of a band stores rows RPI_O*t + lane/CPRO; the
+        // chunk a lane holds there is (lane % CPRO) ^ row = c0 ^ (RPI_O*t) (row < 16, RPI_O*t has
+        // no bit in common with lane/CPRO), so the per-lane offsets of the NST instructions are the
+        // same for every band and the band's row offset is a scalar.
+        constexpr int RPI_O = 1024 / RPB;            // rows per store instruction
+        constexpr int NST = BAND / RPI_O;            // store instructions per band and output
+        const int mv_w = min(TM, mvalid - wrow0), nv_w = min(TN, nvalid - wcol0);
+        const int obytes = __builtin_amdgcn_readfirstlane(
+            (mv_w > 0 && nv_w > 0) ? ((mv_w - 1) * (int)ldo + nv_w) * ESZ : 0);
+        const size_t o0 = ((size_t)(m0 + wrow0) * ldo + (size_t)(n0 + wcol0)) * ESZ;
+        // (wave-uniform, but derived from the wave number: say so, or every store is wrapped in a loop
+        // over the distinct resources of the lanes)
+        auto uniform_ptr = [](uint8_t* p_) {
+            const uint64_t b = (uint64_t)p_;
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
+            return (uint8_t*)(((uint64_t)hi << 32) | lo);
+        };
+        uint8_t* obase0 = TOKENS ? reinterpret_cast<uint8_t*>(tok_out) : reinterpret_cast<uint8_t*>(g.out0);
+        const __amdgpu_buffer_rsrc_t ro0 = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(obase0 + o0), 0, obytes, 0x00020000);
+        __amdgpu_buffer_rsrc_t ro1 = ro0;
+        if constexpr (OP == OP_FC1)
+            ro1 = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(reinterpret_cast<uint8_t*>(g.out1) + o0), 0, obytes, 0x00020000);
+        const int ldo_b = __builtin_amdgcn_readfirstlane((int)ldo * ESZ);   // bytes per output row
+        int ovoff[NST];
+        {
+            const int q = lane / CPRO, c0 = (lane % CPRO) ^ q;
+#pragma unroll
+            for (int t = 0; t < NST; ++t) {
+                const int c = c0 ^ (RPI_O * t);
+                ovoff[t] = c * 16 < nv_w * ESZ ? q * (int)ldo * ESZ + c * 16 : (int)0x80000000;
+            }
+        }
         stage_pre(0, 0);
         float cs0 = 0.f, cs1 = 0.f;   // DGRAD2: sums of columns 2*lane, 2*lane+1 over this wave's rows (ESS, Table 5 row 8)
 #pragma unroll
@@ -703,6 +742,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
             // -- registers -> LDS band
+            // (the band's accumulators are claimed in their accumulation registers at this point:
+            // otherwise the register allocator permutes and copies a few hundred of them ahead of
+            // the first band)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int col = j * 16 + 4 * grp;                  // column inside the wave tile
@@ -757,26 +801,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 }
             }
             // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
-            constexpr int RPI_O = 1024 / RPB;            // rows per instruction
 #pragma unroll
-            for (int t = 0; t < BAND / RPI_O; ++t) {
-                const int row = RPI_O * t + lane / CPRO;
-                const int c = (lane % CPRO) ^ row;       // row < 16 <= CPRO
-                const int col = wcol0 + c * (16 / ESZ);
-                const int trow = wrow0 + i * BAND + row;
-                const bool ok = trow < mvalid && col < nvalid;
-                const size_t oi = (size_t)(m0 + trow) * ldo + (size_t)(n0 + col);
+            for (int t = 0; t < NST; ++t) {
+                const int soff = (i * BAND + RPI_O * t) * ldo_b;
                 const u32x4 d0 = *reinterpret_cast<const u32x4*>(wreg + t * 1024 + lane * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(d0, ro0, ovoff[t], soff, 0);
                 if constexpr (OP == OP_FC1) {
                     const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + H_OFF + t * 1024 + lane * 16);
-                    if (ok) {
-                        STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
-                        STORE16(reinterpret_cast<bf16_t*>(g.out1) + oi, d1);
-                    }
-                } else if constexpr (TOKENS) {
-                    if (ok) STORE16(tok_out + oi, d0);
-                } else {
-                    if (ok) STORE16(reinterpret_cast<bf16_t*>(g.out0) + oi, d0);
+                    __builtin_amdgcn_raw_buffer_store_b128(d1, ro1, ovoff[t], soff, 0);
                 }
             }
         }
@@ -787,7 +819,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                     make_float2(cs0, cs1);
         }
     }
-#undef STORE16
 }
 
 template <int BM, int BN, int WM, int WN, int OP, int ACT = HEXA_ACT_GELU_TANH, bool F16 = false>
