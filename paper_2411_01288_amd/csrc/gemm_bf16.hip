@@ -451,12 +451,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         }
     }
 
-    f32x4 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
     // ---- per-lane fragment addresses -----------------------------------------------------------
     // A 16x16x32 MFMA operand fragment: lane (l16, grp) holds k = 8*grp + 0..7 of row (or column) l16
     // of its 16-wide block.
@@ -605,6 +599,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 2 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(k1, o); }
         _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 3 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(k1, o); }
     }
+    // The accumulators are cleared here, between the first requests and the wait for them: claimed
+    // in their accumulation registers by the empty statements (which keep their place among the
+    // other volatile statements), the 256 writes run while the first block is on its way instead of
+    // after it has arrived.
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jj = 0; jj < FN; ++jj) {
+            acc[i][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+            asm volatile("" : "+a"(acc[i][jj]));
+        }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA + NIB) : "memory");
     __syncthreads();
     _Pragma("unroll") for (int r = 0; r < NRD; ++r) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, r);

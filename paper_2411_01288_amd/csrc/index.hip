@@ -69,9 +69,18 @@ __global__ __launch_bounds__(1024) void index_scan(int32_t* __restrict__ hist, i
     const int e = t % E, g = t / E;
     const bool active = g < G;
     const int c0 = g * cpg, c1 = min(nchunks, c0 + cpg);
+    // (both passes over this thread's chunks go eight loads at a time: one at a time, the kernel is
+    // a chain of memory latencies)
     int s = 0;
-    if (active)
-        for (int c = c0; c < c1; ++c) s += hist[(size_t)c * E + e];
+    if (active) {
+        for (int c = c0; c < c1; c += 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = c + u < c1 ? hist[(size_t)(c + u) * E + e] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+    }
     if (active) gs[g * E + e] = s;
     __syncthreads();
     int base = 0;
@@ -99,11 +108,15 @@ __global__ __launch_bounds__(1024) void index_scan(int32_t* __restrict__ hist, i
     __syncthreads();
     if (active) {
         int run = cnt[e] + base;
-        for (int c = c0; c < c1; ++c) {
-            const size_t i = (size_t)c * E + e;
-            const int v = hist[i];
-            hist[i] = run;
-            run += v;
+        for (int c = c0; c < c1; c += 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = c + u < c1 ? hist[(size_t)(c + u) * E + e] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (c + u < c1) hist[(size_t)(c + u) * E + e] = run;
+                run += v[u];
+            }
         }
     }
 }
