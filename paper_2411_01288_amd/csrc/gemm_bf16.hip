@@ -675,7 +675,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         constexpr int RPB = TN * ESZ;                 // bytes per staged row (TN columns)
         constexpr int CPRO = RPB / 16;                // 16-byte chunks per staged row
         constexpr int BAND = 16;                      // rows per band = rows of an MFMA block
-        constexpr int H_OFF = 8192;                   // FC1: second output band
+        constexpr int H_OFF = BAND * RPB;             // FC1: second output of a band, behind the first
         constexpr int G_OFF = 16384, G_BUF = BAND * 256;   // DGRAD2: two bands of saved derivatives
         static_assert(TN == 128, "epilogue staging is laid out for 128-column wave tiles");
         const size_t ldo = (size_t)g.N;
@@ -738,11 +738,56 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         }
         stage_pre(0, 0);
         float cs0 = 0.f, cs1 = 0.f;   // DGRAD2: sums of columns 2*lane, 2*lane+1 over this wave's rows (ESS, Table 5 row 8)
+        // The bands run as a two-stage pipeline over two LDS band buffers: the reads that fetch band
+        // i-1 back from LDS are issued before the arithmetic of band i and their results are stored
+        // (and, DGRAD2, added up) after it, so neither the write-to-read turn-around of LDS nor the
+        // latency of the reads is waited for.  LDS executes a wave's instructions in order, so the
+        // writes of band i+1 cannot overtake the reads of band i-1 from the same buffer.
+        constexpr int BAND_BYTES = BAND * RPB;
+        constexpr int BUF_STRIDE = (OP == OP_FC1 ? 2 : 1) * BAND_BYTES;   // FC1 stages two outputs per band
+        static_assert(H_OFF == BAND_BYTES && 2 * BUF_STRIDE <= G_OFF, "band buffers overlap");
+        u32x4 d0[NST], d1[OP == OP_FC1 ? NST : 1];
+        uint32_t cw[OP == OP_DGRAD2 ? BAND : 1];
+        auto band_reads = [&](int buf) __attribute__((always_inline)) {
+            uint8_t* wb = wreg + buf * BUF_STRIDE;
+#pragma unroll
+            for (int t = 0; t < NST; ++t) {
+                d0[t] = *reinterpret_cast<const u32x4*>(wb + t * 1024 + lane * 16);
+                if constexpr (OP == OP_FC1) d1[t] = *reinterpret_cast<const u32x4*>(wb + H_OFF + t * 1024 + lane * 16);
+            }
+            if constexpr (OP == OP_DGRAD2) {
+                // bias-gradient partial: the band holds the rounded dpre values the weight gradient
+                // will read; rows past the segment and columns past N are exact zeros
+#pragma unroll
+                for (int row = 0; row < BAND; ++row)
+                    cw[row] = *reinterpret_cast<const uint32_t*>(
+                        wb + row * RPB + ((((lane >> 2) ^ row)) << 4) + (lane & 3) * 4);
+            }
+        };
+        auto band_stores = [&](int i) __attribute__((always_inline)) {
+#pragma unroll
+            for (int t = 0; t < NST; ++t) {
+                const int soff = (i * BAND + RPI_O * t) * ldo_b;
+                __builtin_amdgcn_raw_buffer_store_b128(d0[t], ro0, ovoff[t], soff, 0);
+                if constexpr (OP == OP_FC1) __builtin_amdgcn_raw_buffer_store_b128(d1[t], ro1, ovoff[t], soff, 0);
+            }
+            if constexpr (OP == OP_DGRAD2) {
+#pragma unroll
+                for (int row = 0; row < BAND; ++row) {
+                    float c0, c1;
+                    unpack2<F16>(cw[row], c0, c1);
+                    cs0 += c0; cs1 += c1;
+                }
+            }
+        };
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
+            uint8_t* wb = wreg + (i & 1) * BUF_STRIDE;
+            if (i > 0) band_reads((i - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
             if constexpr (OP == OP_DGRAD2) {
                 // the next band's derivatives are requested before this band's are awaited; the
-                // counter also holds the previous band's stores, which are older than both
+                // counter also holds stores of earlier bands, which are older than both
                 if (i + 1 < FM) stage_pre(i + 1, (i + 1) & 1);
                 if (i + 1 < FM) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GI) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -765,7 +810,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                 }
                 if constexpr (OUT_F32) {
                     const int c = col >> 2;
-                    *reinterpret_cast<float4*>(wreg + l16 * RPB + ((c ^ l16) << 4)) =
+                    *reinterpret_cast<float4*>(wb + l16 * RPB + ((c ^ l16) << 4)) =
                         make_float4(v[0], v[1], v[2], v[3]);
                 } else {
                     const int c = col >> 3;
@@ -777,12 +822,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         u32x2 pz, hz;
                         pz.x = pack2<F16>(gg[0], gg[1]); pz.y = pack2<F16>(gg[2], gg[3]);
                         hz.x = pack2<F16>(hh[0], hh[1]); hz.y = pack2<F16>(hh[2], hh[3]);
-                        *reinterpret_cast<u32x2*>(wreg + off) = pz;
-                        *reinterpret_cast<u32x2*>(wreg + H_OFF + off) = hz;
+                        *reinterpret_cast<u32x2*>(wb + off) = pz;
+                        *reinterpret_cast<u32x2*>(wb + H_OFF + off) = hz;
                     } else if constexpr (OP == OP_FC2 || OP == OP_DGRAD1) {
                         u32x2 z;
                         z.x = pack2<F16>(v[0], v[1]); z.y = pack2<F16>(v[2], v[3]);
-                        *reinterpret_cast<u32x2*>(wreg + off) = z;
+                        *reinterpret_cast<u32x2*>(wb + off) = z;
                     } else {   // DGRAD2
                         const u32x2 pp = *reinterpret_cast<const u32x2*>(wreg + G_OFF + (i & 1) * G_BUF + off);
                         float p0, p1, p2, p3;
@@ -790,34 +835,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         u32x2 d;
                         d.x = pack2<F16>(v[0] * p0, v[1] * p1);
                         d.y = pack2<F16>(v[2] * p2, v[3] * p3);
-                        *reinterpret_cast<u32x2*>(wreg + off) = d;
+                        *reinterpret_cast<u32x2*>(wb + off) = d;
                     }
                 }
             }
-            if constexpr (OP == OP_DGRAD2) {
-                // bias-gradient partial: the band holds the rounded dpre values the weight gradient
-                // will read; rows past the segment and columns past N are exact zeros
-#pragma unroll 8
-                for (int row = 0; row < BAND; ++row) {
-                    const uint32_t w2 = *reinterpret_cast<const uint32_t*>(
-                        wreg + row * RPB + ((((lane >> 2) ^ row)) << 4) + (lane & 3) * 4);
-                    float c0, c1;
-                    unpack2<F16>(w2, c0, c1);
-                    cs0 += c0; cs1 += c1;
-                }
-            }
+            __builtin_amdgcn_sched_barrier(0);
             // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
-#pragma unroll
-            for (int t = 0; t < NST; ++t) {
-                const int soff = (i * BAND + RPI_O * t) * ldo_b;
-                const u32x4 d0 = *reinterpret_cast<const u32x4*>(wreg + t * 1024 + lane * 16);
-                __builtin_amdgcn_raw_buffer_store_b128(d0, ro0, ovoff[t], soff, 0);
-                if constexpr (OP == OP_FC1) {
-                    const u32x4 d1 = *reinterpret_cast<const u32x4*>(wreg + H_OFF + t * 1024 + lane * 16);
-                    __builtin_amdgcn_raw_buffer_store_b128(d1, ro1, ovoff[t], soff, 0);
-                }
-            }
+            if (i > 0) band_stores(i - 1);
         }
+        band_reads((FM - 1) & 1);
+        band_stores(FM - 1);
         if constexpr (OP == OP_DGRAD2) {
             const int col = wcol0 + 2 * lane;
             if (col < nvalid)
