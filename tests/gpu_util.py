@@ -57,7 +57,7 @@ def nrm_err(got, ref):
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     err = float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
-    log = os.environ.get("HEXA_ERR_LOG")      # optional: one line per comparison, for the error survey in the design notes
+    log = os.environ.get("HEXA_ERR_LOG")      # optional: one line per comparison (a survey of the errors actually met)
     if log:
         with open(log, "a") as f:
             f.write(f"{err:.3e}\t{os.environ.get('PYTEST_CURRENT_TEST', '')}\n")
