@@ -972,11 +972,16 @@ hipError_t gemm_bf16_device_init() {
 int gemm_row_tile() { return TBM; }
 int gemm_colpart_rows_per_tile() { return TWM; }
 
-// Tokens per split-K chunk of the token contractions: long enough that most experts are one
-// chunk (no partial traffic), short enough that ~4 items per CU exist under skewed routing.
+// Tokens per split-K chunk of the token contractions: an expert is cut only when its rows alone
+// would give every CU a tile's worth of work for longer than the whole contraction takes on
+// average (chunk = the rows that make one tile per CU of the chip: A * tiles / CUs).  Shorter chunks
+// balance no better, because the grid is shared with the row GEMM of the same layer, whose tiles
+// fill the gaps, and every extra chunk costs a partial d x f tile written and read back (measured:
+// a quarter of this length made C3 5.6 %, C4 1.9 % and C5 under Zipf routing 0.5 % slower; half
+// as many chunks again made C3 and C4 slower).
 int wgrad_chunk_len(const MoeDims& D) {
     const long long tmn = (long long)ceil_div(D.d, TBM) * ceil_div(D.f, TBN);
-    long long L = (long long)D.A * tmn / (4 * kNumCUs);
+    long long L = (long long)D.A * tmn / kNumCUs;
     L = (L + 63) / 64 * 64;
     if (L < 1024) L = 1024;
     // one item's rows are addressed with 32-bit byte offsets: L * max(d, f) * 2 < 2^32
