@@ -184,27 +184,46 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ src, 
     partial[(size_t)blockIdx.x * ncols + c] = acc;
 }
 
-// Stage 2: out[e][c] = sum of the expert's tile partials in tile order (exact 0 for an empty expert).
-__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int ncols,
-                                                     int E, int tile_rows,
+// Stage 2: out[e][c] = sum of the expert's partial rows (exact 0 for an empty expert).  The expert's
+// tiles (tile height bm, `parts` partial rows per tile) hold rows first*parts .. (first+nt)*parts - 1
+// of `partial`.  A workgroup is 64 columns x 4 slices: slice s adds up a contiguous quarter of the
+// rows in order, and the four slice sums are added in slice order, so the result does not depend
+// on scheduling; one thread per column walking all rows alone was a chain of up to 800 dependent
+// memory latencies for a large expert.
+__global__ __launch_bounds__(256) void colsum_finish(const float* __restrict__ partial, int ncols,
+                                                     int E, int bm, int parts,
                                                      const int32_t* __restrict__ offsets,
                                                      float* __restrict__ out) {
+    __shared__ float part[4][64];
     const int e = blockIdx.x;
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    if (c >= ncols) return;
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int c = blockIdx.y * 64 + lane;
     int first = 0;
-    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], tile_rows);
-    const int nt = ceil_div(offsets[e + 1] - offsets[e], tile_rows);
+    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], bm);
+    const int nrows = ceil_div(offsets[e + 1] - offsets[e], bm) * parts;
+    const int per = ceil_div(nrows, 4);
+    const int r0 = min(nrows, slice * per), r1 = min(nrows, r0 + per);
     float acc = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < nt; ++i) acc += partial[(size_t)(first + i) * ncols + c];
-    out[(size_t)e * ncols + c] = acc;
+    if (c < ncols) {
+        const float* src = partial + (size_t)first * parts * ncols + c;
+        for (int i = r0; i < r1; i += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i + u < r1 ? src[(size_t)(i + u) * ncols] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+    }
+    part[slice][lane] = acc;
+    __syncthreads();
+    if (slice == 0 && c < ncols)
+        out[(size_t)e * ncols + c] = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
 }
 
 // Backward prologue and the fc2 bias gradient in one pass (ESS, Sec. 3.1 item 2; Table 5 row 4):
 // one workgroup per segment tile of tile_rows <= 128 rows; a thread owns VN consecutive columns (256*VN columns per
 // sweep) and walks the tile's rows in order, so the column sums of do = gate * dY (unrounded) stay
-// in registers and go to partial[tile][col] for colsum_stage2.  Per row it also writes
+// in registers and go to partial[tile][col] for colsum_finish.  Per row it also writes
 // dout_p = round(do), xg_p = x_t and accumulates <dY_t, o_p> (wave sums meet in LDS, added in wave
 // order).  Workgroups past the last tile zero the rows past the last segment (they exist only
 // when expert ids were dropped).  d % VN == 0.
@@ -281,24 +300,6 @@ __global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, c
     }
 }
 
-// out[e][c] = sum over the expert's row tiles (tile height bm, `parts` partial rows per tile) of
-// partial[tile*parts + q][c], in order; exact 0 for an expert without rows.
-__global__ __launch_bounds__(256) void tile_colsum_finish(const float* __restrict__ partial, int ncols,
-                                                          int E, int bm, int parts,
-                                                          const int32_t* __restrict__ offsets,
-                                                          float* __restrict__ out) {
-    const int e = blockIdx.x;
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    if (c >= ncols) return;
-    int first = 0;
-    for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], bm);
-    const int nt = ceil_div(offsets[e + 1] - offsets[e], bm);
-    float acc = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < nt * parts; ++i) acc += partial[(size_t)(first * parts + i) * ncols + c];
-    out[(size_t)e * ncols + c] = acc;
-}
-
 template <typename T>
 hipError_t combine_impl(int T_, int d, int k, const T* src, const int32_t* inv,
                         const float* gate, T* dst, hipStream_t st) {
@@ -360,8 +361,8 @@ hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg,
                                D.k, dY, x, xg, o, perm, offsets, D.E, gate, dout, dgate, partial, R);
         }
         ProfScope ps(st, "colsum_db2");
-        hipLaunchKernelGGL(colsum_stage2, dim3(D.E, ceil_div(D.d, 256)), dim3(256), 0, st, partial, D.d,
-                           D.E, R, offsets, db2);
+        hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(D.d, 64)), dim3(256), 0, st, partial, D.d,
+                           D.E, R, 1, offsets, db2);
         return hipGetLastError();
     }
     {
@@ -380,15 +381,15 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
     ProfScope ps(st, ncols == D.d ? "colsum_db2" : "colsum_db1");
     hipLaunchKernelGGL(colsum_stage1<T>, dim3(max_tiles, cb), dim3(256), 0, st, src, ncols, D.E,
                        offsets, partial);
-    hipLaunchKernelGGL(colsum_stage2, dim3(D.E, cb), dim3(256), 0, st, partial, ncols, D.E, kColsumRows, offsets,
-                       out);
+    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 64)), dim3(256), 0, st, partial, ncols, D.E,
+                       kColsumRows, 1, offsets, out);
     return hipGetLastError();
 }
 
 hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int ncols,
                                      const int32_t* offsets, float* out, hipStream_t st) {
     ProfScope ps(st, "colsum_db1");
-    hipLaunchKernelGGL(tile_colsum_finish, dim3(D.E, ceil_div(ncols, 256)), dim3(256), 0, st, partial, ncols,
+    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 64)), dim3(256), 0, st, partial, ncols,
                        D.E, gemm_row_tile(), gemm_colpart_rows_per_tile(), offsets, out);
     return hipGetLastError();
 }
