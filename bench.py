@@ -96,8 +96,8 @@ def hbm_steps(w, kernels, copy_gbps):
     algo = {
         # y_t = sum_j g o_a: o [A,d] and inv, gate in; y [T,d] out
         "combine_y": A * d * es + T * d * es + A * 8,
-        # dY (gathered), o, x in; dout, xg out (+ dgate, column-sum partials)
-        "bwd_prologue": A * d * es * (5 if w.dtype != "f32" else 3) + A * 12,
+        # dY (gathered) and o in; dout out (+ perm, gate, dgate)
+        "bwd_prologue": A * d * es * 3 + A * 12,
         "combine_dx": A * d * es + T * d * es + A * 4,
         "index_scatter": A * 4 + A * 8,
     }

@@ -65,7 +65,8 @@ def lint_staging_hazards(src: str = "gemm_bf16.hip") -> None:
     not see them.  One hazard matters: a vector-memory instruction must not read a scalar register
     within five wait states of a VECTOR instruction writing it (v_readfirstlane of a uniform value
     kept in vector registers, v_readlane of a spilled scalar).  This reads the generated ISA and
-    refuses the build if a staging load reads such a register too early."""
+    refuses the build if a staging load (or a global load with a scalar base, the form of the
+    row-offset loads) reads such a register too early."""
     res = subprocess.run(["hipcc", *FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", "-"],
                          stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
     if res.returncode != 0:
@@ -79,7 +80,7 @@ def lint_staging_hazards(src: str = "gemm_bf16.hip") -> None:
                 window = []          # a label: the predecessors are unknown, start over
             continue
         op = t.split()[0]
-        if op.startswith("buffer_load") and t.endswith("lds"):
+        if (op.startswith("buffer_load") and t.endswith("lds")) or (op.startswith("global_load") and "s[" in t):
             need, used = 5, _sgprs(t.split(None, 1)[1])
             for states, written in reversed(window):
                 if need <= 0:

@@ -25,7 +25,7 @@ hexa_status hexa_check_shape(const hexa_moe_shape* s, MoeDims* D) {
         // one 256-row tile of any activation matrix with 32-bit byte offsets; the output window of a
         // tile (256 rows of fp32 at most) must stay below 2^31 bytes, the offset that masks a lane
         const unsigned long long wide = (unsigned long long)(s->d_model > s->d_ff ? s->d_model : s->d_ff);
-        if ((unsigned long long)s->T * s->d_model * 2ull > 0xffffffffull ||
+        if ((unsigned long long)s->T * s->d_model * 2ull > 0xffff0000ull ||   // (+ a tile row must still fit behind the last row)
             (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull ||
             256ull * wide * 4ull > 0x7fffffffull)
             return HEXA_ERR_UNSUPPORTED;
@@ -63,7 +63,7 @@ MoeWorkspace layout(const MoeDims& D, int dtype, void* base) {
         w.colpart = (float*)take(rows * (d > f ? d : f) * 4);
     }
     if (dtype != HEXA_F32) {
-        w.xg = take(A * d * es);
+        w.rowoff = (uint32_t*)take((A + 64 * (size_t)D.E) * 4);
         w.kpart_slots = wgrad_max_slots(D);
         w.kpart = (float*)take(w.kpart_slots * d * f * 4);
         w.worklist = (int32_t*)take(gemm_worklist_ints(D) * 4);
@@ -243,7 +243,7 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
     hipError_t e;
     if (shape->dtype != HEXA_F32 && (e = ensure_device_init()) != hipSuccess) return dev(e);
     if (shape->dtype == HEXA_F32) {
-        e = launch_bwd_prologue<float>(D, (const float*)dY, nullptr, nullptr, (const float*)ws.o, idx.perm,
+        e = launch_bwd_prologue<float>(D, (const float*)dY, (const float*)ws.o, idx.perm,
                                        idx.offsets, gate, (float*)ws.dout, dgate, ws.colpart, db2, st);
         if (e == hipSuccess)
             e = launch_f32_bwd(D, (const float*)x, (const float*)W1, (const float*)W2, idx, ws, dW1, dW2, st);
@@ -253,13 +253,13 @@ hexa_status hexa_moe_bwd(const hexa_moe_shape* shape, const void* dY, const void
     } else {
         const bool f16 = shape->dtype == HEXA_F16;
         if (f16)
-            e = launch_bwd_prologue<f16_t>(D, (const f16_t*)dY, (const f16_t*)x, (f16_t*)ws.xg, (const f16_t*)ws.o,
+            e = launch_bwd_prologue<f16_t>(D, (const f16_t*)dY, (const f16_t*)ws.o,
                                            idx.perm, idx.offsets, gate, (f16_t*)ws.dout, dgate, ws.colpart, db2, st);
         else
-            e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)x, (bf16_t*)ws.xg, (const bf16_t*)ws.o,
+            e = launch_bwd_prologue<bf16_t>(D, (const bf16_t*)dY, (const bf16_t*)ws.o,
                                             idx.perm, idx.offsets, gate, (bf16_t*)ws.dout, dgate, ws.colpart, db2, st);
         if (e == hipSuccess)
-            e = launch_bf16_bwd(D, (const bf16_t*)ws.xg, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
+            e = launch_bf16_bwd(D, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W2, idx, ws,
                                 dW1, dW2, st, f16);
         if (e == hipSuccess)
             e = launch_tile_colsum_finish(D, ws.colpart, D.f, idx.offsets, db1, st);

@@ -132,7 +132,7 @@ struct MoeWorkspace {
     void* dout;     // [A,d] elem   gate * dY gathered to perm order   (bwd staging)
     void* dpre;     // [A,f] elem                                       (bwd staging)
     void* dxp;      // [A,d] elem   per-assignment input gradients     (bwd staging)
-    void* xg;       // [A,d] elem   x gathered to perm order (bf16 path)(bwd staging)
+    uint32_t* rowoff; // [A + 64 E]  byte offsets in x of the token rows, in the order WGRAD1 fetches them (16-bit path; bwd staging)
     float* colpart; // [rows, max(d,f)] f32 partial column sums          (bwd staging)
     float* kpart;   // split-K partial weight-gradient tiles           (bwd staging)
     size_t kpart_slots;
@@ -157,10 +157,10 @@ hipError_t launch_padded_index(const MoeDims& D, const hexa_moe_idx& idx, int bl
 template <typename T>
 hipError_t launch_combine_y(const MoeDims& D, const T* o, const int32_t* inv, const float* gate,
                             T* y, hipStream_t st);
-// dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, (when xg != NULL) xg_p = x_t, for a = perm[p], and
+// dout_p = gate_a dY_t, dgate_a = <dY_t, o_p>, for a = perm[p], and
 // db2[e] = sum over the expert's rows of gate_a dY_t (ESS; `partial` is column-sum staging)
 template <typename T>
-hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
                                T* dout, float* dgate, float* partial, float* db2, hipStream_t st);
 template <typename T>

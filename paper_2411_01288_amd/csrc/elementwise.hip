@@ -107,7 +107,6 @@ __global__ __launch_bounds__(256) void combine_rows_scalar(int T_, int d, int k,
 // One wavefront per perm row p.
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T* __restrict__ dY,
-                                                    const T* __restrict__ x, T* __restrict__ xg,
                                                     const T* __restrict__ o,
                                                     const int32_t* __restrict__ perm,
                                                     const int32_t* __restrict__ offsets, int E,
@@ -118,10 +117,7 @@ __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T
     if (p >= A) return;
     const int n_valid = offsets[E];
     if (p >= n_valid) {  // rows past the last segment exist only when ids were dropped
-        for (int c = lane; c < d; c += 64) {
-            Elem<T>::st(dout + (size_t)p * d + c, 0.f);
-            if (xg) Elem<T>::st(xg + (size_t)p * d + c, 0.f);
-        }
+        for (int c = lane; c < d; c += 64) Elem<T>::st(dout + (size_t)p * d + c, 0.f);
         return;
     }
     const int a = perm[p];
@@ -142,16 +138,12 @@ __global__ __launch_bounds__(256) void bwd_prologue(int A, int d, int k, const T
 #pragma unroll
             for (int q = 0; q < VN; ++q) w[q] = g * v[q];
             Vec<T>::store(dst + c, w);
-            if (xg)
-                *reinterpret_cast<uint4*>(xg + (size_t)p * d + c) =
-                    *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
         }
     } else {
         for (int c = lane; c < d; c += 64) {
             const float v = Elem<T>::ld(src + c);
             dot += v * Elem<T>::ld(orow + c);
             Elem<T>::st(dst + c, g * v);
-            if (xg) xg[(size_t)p * d + c] = x[(size_t)t * d + c];
         }
     }
     if (dgate) {
@@ -224,12 +216,11 @@ __global__ __launch_bounds__(256) void colsum_finish(const float* __restrict__ p
 // one workgroup per segment tile of tile_rows <= 128 rows; a thread owns VN consecutive columns (256*VN columns per
 // sweep) and walks the tile's rows in order, so the column sums of do = gate * dY (unrounded) stay
 // in registers and go to partial[tile][col] for colsum_finish.  Per row it also writes
-// dout_p = round(do), xg_p = x_t and accumulates <dY_t, o_p> (wave sums meet in LDS, added in wave
+// dout_p = round(do) and accumulates <dY_t, o_p> (wave sums meet in LDS, added in wave
 // order).  Workgroups past the last tile zero the rows past the last segment (they exist only
 // when expert ids were dropped).  d % VN == 0.
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, const T* __restrict__ dY,
-                                                          const T* __restrict__ x, T* __restrict__ xg,
                                                           const T* __restrict__ o,
                                                           const int32_t* __restrict__ perm,
                                                           const int32_t* __restrict__ offsets, int E,
@@ -247,10 +238,7 @@ __global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, c
 #pragma unroll
         for (int q = 0; q < VN; ++q) z[q] = 0.f;
         for (long long r = r0; r < r0 + tile_rows && r < A; ++r)
-            for (int c = tid * VN; c < d; c += 256 * VN) {
-                Vec<T>::store(dout + (size_t)r * d + c, z);
-                if (xg) Vec<T>::store(xg + (size_t)r * d + c, z);
-            }
+            for (int c = tid * VN; c < d; c += 256 * VN) Vec<T>::store(dout + (size_t)r * d + c, z);
         return;
     }
     for (int c0 = 0; c0 < d; c0 += 256 * VN) {
@@ -276,9 +264,6 @@ __global__ __launch_bounds__(256) void bwd_prologue_tiles(int A, int d, int k, c
                     cs[q] += w[q];
                 }
                 Vec<T>::store(dout + (size_t)p * d + c, w);
-                if (xg)
-                    *reinterpret_cast<uint4*>(xg + (size_t)p * d + c) =
-                        *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
             }
             if (dgate) {
 #pragma unroll
@@ -345,7 +330,7 @@ hipError_t launch_combine_dx(const MoeDims& D, const T* dxp, const int32_t* inv,
 }
 
 template <typename T>
-hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg, const T* o,
+hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* o,
                                const int32_t* perm, const int32_t* offsets, const float* gate,
                                T* dout, float* dgate, float* partial, float* db2, hipStream_t st) {
     if (dgate) {  // dropped assignments keep a defined (zero) gate gradient
@@ -358,7 +343,7 @@ hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg,
         {
             ProfScope ps(st, "bwd_prologue");
             hipLaunchKernelGGL(bwd_prologue_tiles<T>, dim3(D.A / R + D.E + 1), dim3(256), 0, st, D.A, D.d,
-                               D.k, dY, x, xg, o, perm, offsets, D.E, gate, dout, dgate, partial, R);
+                               D.k, dY, o, perm, offsets, D.E, gate, dout, dgate, partial, R);
         }
         ProfScope ps(st, "colsum_db2");
         hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(D.d, 64)), dim3(256), 0, st, partial, D.d,
@@ -368,7 +353,7 @@ hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* x, T* xg,
     {
         ProfScope ps(st, "bwd_prologue");
         hipLaunchKernelGGL(bwd_prologue<T>, dim3(ceil_div(D.A, 4)), dim3(256), 0, st, D.A, D.d, D.k, dY,
-                           x, xg, o, perm, offsets, D.E, gate, dout, dgate);
+                           o, perm, offsets, D.E, gate, dout, dgate);
     }
     return launch_segment_colsum<T>(D, dout, D.d, offsets, partial, db2, st);
 }
@@ -399,7 +384,7 @@ hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int
                                             const float*, T*, hipStream_t);                        \
     template hipError_t launch_combine_dx<T>(const MoeDims&, const T*, const int32_t*, T*,         \
                                              hipStream_t);                                         \
-    template hipError_t launch_bwd_prologue<T>(const MoeDims&, const T*, const T*, T*,             \
+    template hipError_t launch_bwd_prologue<T>(const MoeDims&, const T*,                           \
                                                const T*, const int32_t*, const int32_t*,           \
                                                const float*, T*, float*, float*, float*,           \
                                                hipStream_t);                                       \

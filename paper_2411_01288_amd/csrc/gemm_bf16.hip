@@ -9,7 +9,7 @@
 //       DGRAD1  dxp = dpre W1[e]^T      (stored as bf16)                 K = f, N = d
 //   token contractions (ESTMM, App. B Alg. 4): the sum runs over one expert's rows
 //       WGRAD2  dW2[e] = h^T do                                      M = f, N = d
-//       WGRAD1  dW1[e] = xg^T dpre                                   M = d, N = f
+//       WGRAD1  dW1[e] = x[perm/k]^T dpre  (token rows gathered)      M = d, N = f
 //
 // What is kept from the paper: rows of a tile all belong to one expert, so a tile needs one
 // expert's weights; rows are addressed through the re-index vector, so nothing is padded to a
@@ -48,6 +48,7 @@ struct GemmArgs {
                           // token contraction: [A][M] perm order
     const bf16_t* B;      // row GEMM: weights [E][..]; token contraction: [A][N] perm order
     const int32_t* perm;  // FC1 gather
+    const uint32_t* rowoff;  // WGRAD1 gather: byte offsets of the token rows, see build_rowoff
     const int32_t* offsets;
     const bf16_t* bias;   // [E][N] or NULL
     const bf16_t* pre_in; // DGRAD2: the saved GELU'(pre)
@@ -212,16 +213,21 @@ struct StageKS {
     // instruction i of a wave covers k-rows RPI*wave + kin + 8 i: (k & 3) is the same for all i and
     // ((k >> 3) & 1) = i & 1, so a lane needs two offsets (even and odd i)
     struct Lane { uint32_t voff[2]; };
-    __device__ static __forceinline__ Lane lane_init(int wave, int lane, uint32_t ld_bytes, int col0) {
+    // (row_bytes = 0 when the k-rows are gathered: the row part of the offset then comes from a table)
+    __device__ static __forceinline__ Lane lane_init(int wave, int lane, uint32_t row_bytes, int col0) {
         const int kin = lane / CPR;                          // k-row inside the instruction
         const int k = (RPI * wave + kin);                    // k-row of instruction i = 0  (< 8)
         Lane ln;
 #pragma unroll
         for (int odd = 0; odd < 2; ++odd) {
             const int c = (lane % CPR) ^ ks_key(k + 8 * odd);
-            ln.voff[odd] = (uint32_t)k * ld_bytes + (uint32_t)(col0 + 8 * c) * 2u;
+            ln.voff[odd] = (uint32_t)k * row_bytes + (uint32_t)(col0 + 8 * c) * 2u;
         }
         return ln;
+    }
+    // gathered k-rows: instruction i fetches the rows whose byte offsets are roff[i] (per lane)
+    __device__ static __forceinline__ void load_gathered(rsrc_t r, const uint32_t (&roff)[NI], const Lane& ln, int i) {
+        dtl_load(r, roff[i] + ln.voff[i & 1], 0u);
     }
     __device__ static __forceinline__ void prep(uint32_t lds_slot, int wave, int i) {
         dtl_m0(lds_slot + (uint32_t)(wave + NW * i) * 1024u);
@@ -290,6 +296,31 @@ __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restric
     if (e == E - 1) { wl[0] = s_t[e]; wl[1] = s_c[e]; wl[2] = 0; wl[3] = 0; }
 }
 
+// Row-offset table of the gathered token contraction (WGRAD1 reads x[perm[p] / k] for perm
+// position p; ESTMM, App. B Alg. 4, takes its tokens through the re-index vector the same way).
+// Expert e's part starts at entry offsets[e] + 64 e and is cut into blocks of 64 rows (the K-blocks
+// of the contraction; a chunk starts on a block boundary); inside a block, entry 8 j + i belongs
+// to row 8 i + j, the transposed order in which a lane of the staging instructions needs them.
+// An entry is the byte offset of the token's row in x; entries past the segment's end hold `pad`,
+// an offset behind the last row of x, which the buffer range check turns into zeros.
+__global__ __launch_bounds__(256) void build_rowoff(const int32_t* __restrict__ offsets,
+                                                    const int32_t* __restrict__ perm, int E, int k,
+                                                    uint32_t row_bytes, uint32_t pad, int total,
+                                                    uint32_t* __restrict__ out) {
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= total) return;
+    int lo = 0, hi = E - 1;                       // the last expert whose part starts at or before g
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (offsets[mid] + 64 * mid <= g) lo = mid; else hi = mid - 1;
+    }
+    const int b = offsets[lo], n = offsets[lo + 1] - b;
+    const int local = g - (b + 64 * lo);
+    const int s = local & 63;
+    const int r = (local & ~63) + 8 * (s & 7) + (s >> 3);
+    out[g] = r < n ? (uint32_t)(perm[b + r] / k) * row_bytes : pad;
+}
+
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
@@ -301,6 +332,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     constexpr int FM = TM / 16, FN = TN / 16;   // 16x16 MFMA blocks per wave tile
     constexpr bool TOKENS = (OP == OP_WGRAD2 || OP == OP_WGRAD1);
     constexpr bool B_KS = TOKENS || OP == OP_FC1 || OP == OP_FC2;
+    constexpr bool A_GK = (OP == OP_WGRAD1);   // operand A's k-rows (tokens) are gathered rows of x
     constexpr int SLOT = (BM > BN ? BM : BN) * ROWB;   // bytes of one ring slot (one operand, one block)
     constexpr int SPS = BK / 32;              // k-substeps (one MFMA k = 32 each) per block
     static_assert(TM % 16 == 0 && TN % 16 == 0, "wave tile must be a multiple of 16x16");
@@ -419,12 +451,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     } else {
         // both operands are [tokens][features] in perm order; tokens past this item's range fall
         // outside the resources
+        // (WGRAD1: operand A is x itself, [tokens][M]; the row of perm position p comes from the
+        // offset table, whose entries past a segment's end point behind the last row of x)
         a_ld = (uint32_t)g.M * 2u; b_ld = (uint32_t)g.N * 2u;
-        ra = make_rsrc(g.A + (size_t)kbeg * g.M, (uint32_t)(kend - kbeg) * a_ld);
+        if constexpr (A_GK) ra = make_rsrc(g.A, (uint32_t)g.a_rows * a_ld);
+        else ra = make_rsrc(g.A + (size_t)kbeg * g.M, (uint32_t)(kend - kbeg) * a_ld);
         rb = make_rsrc(g.B + (size_t)kbeg * g.N, (uint32_t)(kend - kbeg) * b_ld);
         a_step = BK * a_ld; b_step = BK * b_ld;
         if constexpr (TOKENS) {
-            lna = SA::lane_init(uwave, lane, a_ld, m0);
+            lna = SA::lane_init(uwave, lane, A_GK ? 0u : a_ld, m0);
             lnb = SB::lane_init(uwave, lane, b_ld, n0);
         }
     }
@@ -434,7 +469,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     const uint32_t a_row = TOKENS ? a_ld : (uint32_t)g.K * 2u, b_row = B_KS ? b_ld : (uint32_t)g.K * 2u;
 #define PREP_A(slot_, i_) SA::prep((slot_), uwave, i_)
 #define PREP_B(slot_, i_) SB::prep((slot_), uwave, i_)
-#define LOAD_A(kt_, i_) SA::load(ra, (kt_) * a_step, a_row, lna, i_)
+#define LOAD_A(kt_, i_)                                                                          \
+    do {                                                                                         \
+        if constexpr (A_GK) SA::load_gathered(ra, rcur, lna, i_);                                \
+        else SA::load(ra, (kt_) * a_step, a_row, lna, i_);                                       \
+    } while (0)
 #define LOAD_B(kt_, i_) SB::load(rb, (kt_) * b_step, b_row, lnb, i_)
 
     // The bias values this lane adds in the epilogue (block j: columns j*16 + 4*grp + 0..3 of the
@@ -592,12 +631,46 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // one row.  The K loop is bottom-tested for that reason: with a zero-trip path the accumulators
     // of the two paths meet behind the loop, and the register allocator shuffles them there.
     const int klast = nk - 1;
+    // WGRAD1: the byte offsets in x of the eight token rows this lane fetches per K-block (instruction
+    // i of a wave covers the block's rows 8 i + 2 wave + lane / 32; the table stores a block's 64
+    // offsets transposed, so those eight are 32 consecutive bytes).  rcur holds the offsets of the
+    // block requested next (block j + 2 during block j); those of the block after it are loaded at
+    // the head of block j and taken over at the wait in its middle, which covers them because they
+    // are older than operand A's requests of that block.  The loads are inline assembly like the
+    // staging requests (own counting of vmcnt).  Their results are tied to the wait statement, so
+    // nothing can read them in front of it, and they do not live across the loop's back edge, where
+    // the compiler would copy them (before they have arrived).
+    uint32_t rcur[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    const uint32_t* rbase = nullptr;   // this item's first table entry (wave-uniform)
+    const uint32_t rl_off = (uint32_t)(8 * (2 * uwave + (lane >> 5))) * 4u;   // this lane's eight entries of a block
+    auto roff_request = [&](int kt, u32x4& lo, u32x4& hi) __attribute__((always_inline)) {
+        const uint32_t* p_ = rbase + (size_t)64 * kt;   // scalar base + lane offset: no vector arithmetic per block
+        asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dwordx4 %1, %2, %3 offset:16"
+                     : "=&v"(lo), "=&v"(hi) : "v"(rl_off), "s"(p_) : "memory");
+    };
+#define ROFF_TAKE(lo_, hi_)                                                                       \
+    do {                                                                                          \
+        rcur[0] = (lo_)[0]; rcur[1] = (lo_)[1]; rcur[2] = (lo_)[2]; rcur[3] = (lo_)[3];           \
+        rcur[4] = (hi_)[0]; rcur[5] = (hi_)[1]; rcur[6] = (hi_)[2]; rcur[7] = (hi_)[3];           \
+    } while (0)
     {
         const uint32_t k1 = (uint32_t)min(1, klast);
+        u32x4 r0_lo, r0_hi, r1_lo, r1_hi, r2_lo, r2_hi;
+        if constexpr (A_GK) {
+            rbase = g.rowoff + (size_t)kbeg + (size_t)64 * e;
+            roff_request(0, r0_lo, r0_hi);
+            roff_request((int)k1, r1_lo, r1_hi);
+            roff_request(min(2, klast), r2_lo, r2_hi);
+            asm volatile("s_waitcnt vmcnt(0)"
+                         : "+v"(r0_lo), "+v"(r0_hi), "+v"(r1_lo), "+v"(r1_hi), "+v"(r2_lo), "+v"(r2_hi) : : "memory");
+            ROFF_TAKE(r0_lo, r0_hi);
+        }
         _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 0 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(0u, o); }
         _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 1 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(0u, o); }
+        if constexpr (A_GK) ROFF_TAKE(r1_lo, r1_hi);
         _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(smem0 + 2 * SLOT, o); asm volatile("s_nop 0"); LOAD_A(k1, o); }
         _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(smem0 + 3 * SLOT, o); asm volatile("s_nop 0"); LOAD_B(k1, o); }
+        if constexpr (A_GK) ROFF_TAKE(r2_lo, r2_hi);
     }
     // The accumulators are cleared here, between the first requests and the wait for them: claimed
     // in their accumulation registers by the empty statements (which keep their place among the
@@ -628,12 +701,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         const uint32_t a2 = smem0 + (uint32_t)(sa2 * SLOT);   // A(j+2): the slot of B(j-1)
         const uint32_t b2 = smem0 + (uint32_t)(sa * SLOT);    // B(j+2): the slot of A(j)
         const uint32_t kreq = (uint32_t)min(j + 2, klast);
+        u32x4 rn_lo, rn_hi;
+        uint32_t rnx[8];   // the same eight values once they have arrived
+        if constexpr (A_GK) roff_request(min(j + 3, klast), rn_lo, rn_hi);
         FENCE();
         SUBSTEP(fa0, fb0, READ_ONE(fa1, fb1, abase, bbase, 1, r), STAGE_AT(m, PREP_A, LOAD_A, a2, kreq));
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
+        if constexpr (A_GK) {
+            asm volatile("s_waitcnt vmcnt(%2)" : "+v"(rn_lo), "+v"(rn_hi) : "n"(NIA) : "memory");
+            rnx[0] = rn_lo[0]; rnx[1] = rn_lo[1]; rnx[2] = rn_lo[2]; rnx[3] = rn_lo[3];
+            rnx[4] = rn_hi[0]; rnx[5] = rn_hi[1]; rnx[6] = rn_hi[2]; rnx[7] = rn_hi[3];
+        } else {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
+        }
         __syncthreads();
         FENCE();
-        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, r), STAGE_AT(m, PREP_B, LOAD_B, b2, kreq));
+        // (WGRAD1 takes the new row offsets over one register per eighth of the substep, each copy in
+        // an issue slot of its own: left to the compiler, the eight copies sit in a row at the
+        // loop's back edge, two MFMAs' worth of issue cycles)
+#define TAKE_AT(m_)                                                                               \
+    do {                                                                                          \
+        if constexpr (A_GK) {                                                                     \
+            if ((m_) % 8 == 5)                                                                    \
+                asm volatile("v_mov_b32 %0, %1" : "=v"(rcur[(m_) / 8]) : "v"(rnx[(m_) / 8]));     \
+        }                                                                                         \
+    } while (0)
+        SUBSTEP(fa1, fb1, READ_ONE(fa0, fb0, anext, bnext, 0, r), STAGE_AT(m, PREP_B, LOAD_B, b2, kreq); TAKE_AT(m));
+#undef TAKE_AT
         sa = sa1; sb = sb1;
     } while (++j < nk);
     // no staging write may still be in flight when the workgroup gives its LDS back
@@ -647,6 +740,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
 #pragma unroll
         for (int jj = 0; jj < FN; ++jj) asm volatile("" : "+a"(acc[i][jj]));
 #undef STAGE_AT
+#undef ROFF_TAKE
 #undef SUBSTEP
 #undef READ_ONE
 #undef READ_A
@@ -1026,7 +1120,7 @@ static hipError_t fwd_impl(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
 }
 
 template <bool F16>
-static hipError_t bwd_impl(const MoeDims& D, const bf16_t* xg, const bf16_t* W1, const bf16_t* W2,
+static hipError_t bwd_impl(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* W2,
                            const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
                            hipStream_t st) {
     GemmArgs g{};
@@ -1034,16 +1128,23 @@ static hipError_t bwd_impl(const MoeDims& D, const bf16_t* xg, const bf16_t* W1,
     g.kpart = ws.kpart; g.chunk_len = wgrad_chunk_len(D);
     // the work lists are the ones the forward pass built (part of the state it saves in the workspace)
     g.worklist = ws.worklist; g.rt_cap = worklist_rt_cap(D);
+    {   // WGRAD1's row-offset table; entries past a segment's end point behind the last row of x
+        ProfScope ps(st, "rowoff");
+        const int total = D.A + 64 * D.E;
+        hipLaunchKernelGGL(build_rowoff, dim3(ceil_div(total, 256)), dim3(256), 0, st, idx.offsets, idx.perm,
+                           D.E, D.k, (uint32_t)D.d * 2u, (uint32_t)D.T * (uint32_t)D.d * 2u, total, ws.rowoff);
+    }
     // 2nd linear layer: dpre = (do W2^T) * F'(pre)  and  dW2[e] = h^T do
     GemmArgs r = g, t = g;
     r.A = (const bf16_t*)ws.dout; r.B = W2; r.pre_in = (const bf16_t*)ws.pre; r.out0 = ws.dpre;
     r.colpart = ws.colpart; r.K = D.d; r.N = D.f;
     t.A = (const bf16_t*)ws.h; t.B = (const bf16_t*)ws.dout; t.out0 = dW2; t.M = D.f; t.N = D.d;
     launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD2, OP_WGRAD2, F16>(D, r, t, st, "bwd_fc2", "wgrad2_finish");
-    // 1st linear layer: dxp = dpre W1^T  and  dW1[e] = xg^T dpre
+    // 1st linear layer: dxp = dpre W1^T  and  dW1[e] = x[perm/k]^T dpre
     r = g; t = g;
     r.A = (const bf16_t*)ws.dpre; r.B = W1; r.out0 = ws.dxp; r.K = D.f; r.N = D.d;
-    t.A = xg; t.B = (const bf16_t*)ws.dpre; t.out0 = dW1; t.M = D.d; t.N = D.f;
+    t.A = x; t.a_rows = D.T; t.rowoff = ws.rowoff;
+    t.B = (const bf16_t*)ws.dpre; t.out0 = dW1; t.M = D.d; t.N = D.f;
     launch_pair<TBM, TBN, TWM, TWN, OP_DGRAD1, OP_WGRAD1, F16>(D, r, t, st, "bwd_fc1", "wgrad1_finish");
     return hipGetLastError();
 }
@@ -1056,9 +1157,9 @@ hipError_t launch_bf16_fwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, 
                : fwd_impl<false>(D, x, W1, b1, W2, b2, idx, ws, st);
 }
 
-hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* xg, const bf16_t* W1, const bf16_t* W2,
+hipError_t launch_bf16_bwd(const MoeDims& D, const bf16_t* x, const bf16_t* W1, const bf16_t* W2,
                            const hexa_moe_idx& idx, const MoeWorkspace& ws, float* dW1, float* dW2,
                            hipStream_t st, bool f16) {
-    return f16 ? bwd_impl<true>(D, xg, W1, W2, idx, ws, dW1, dW2, st)
-               : bwd_impl<false>(D, xg, W1, W2, idx, ws, dW1, dW2, st);
+    return f16 ? bwd_impl<true>(D, x, W1, W2, idx, ws, dW1, dW2, st)
+               : bwd_impl<false>(D, x, W1, W2, idx, ws, dW1, dW2, st);
 }
