@@ -178,38 +178,56 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ src, 
 
 // Stage 2: out[e][c] = sum of the expert's partial rows (exact 0 for an empty expert).  The expert's
 // tiles (tile height bm, `parts` partial rows per tile) hold rows first*parts .. (first+nt)*parts - 1
-// of `partial`.  A workgroup is 64 columns x 4 slices: slice s adds up a contiguous quarter of the
-// rows in order, and the four slice sums are added in slice order, so the result does not depend
-// on scheduling; one thread per column walking all rows alone was a chain of up to 800 dependent
-// memory latencies for a large expert.
-__global__ __launch_bounds__(256) void colsum_finish(const float* __restrict__ partial, int ncols,
+// of `partial`.  A workgroup is 256 columns x up to 16 slices (a lane owns four columns, 64 apart):
+// slice s adds up a contiguous share of the rows in order, and the slice sums are added in slice
+// order, so the result does not depend on scheduling; one thread per column walking all rows alone
+// was a chain of up to 800 dependent memory latencies for a large expert.
+constexpr int kFinishSlices = 16;   // at most (the launch picks 64 * slices threads)
+__global__ __launch_bounds__(64 * kFinishSlices) void colsum_finish(const float* __restrict__ partial, int ncols,
                                                      int E, int bm, int parts,
                                                      const int32_t* __restrict__ offsets,
                                                      float* __restrict__ out) {
-    __shared__ float part[4][64];
+    __shared__ float part[kFinishSlices][256];
     const int e = blockIdx.x;
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int c = blockIdx.y * 64 + lane;
+    const int c0 = blockIdx.y * 256 + lane;
     int first = 0;
     for (int q = 0; q < e; ++q) first += ceil_div(offsets[q + 1] - offsets[q], bm);
     const int nrows = ceil_div(offsets[e + 1] - offsets[e], bm) * parts;
-    const int per = ceil_div(nrows, 4);
+    // as many slices as give each at least eight rows (a function of the expert's row count only)
+    const int nsl = min((int)blockDim.x / 64, max(1, nrows / 8));
+    const int per = ceil_div(nrows, nsl);
     const int r0 = min(nrows, slice * per), r1 = min(nrows, r0 + per);
-    float acc = 0.f;
-    if (c < ncols) {
-        const float* src = partial + (size_t)first * parts * ncols + c;
-        for (int i = r0; i < r1; i += 8) {
-            float v[8];
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const float* src = partial + (size_t)first * parts * ncols;
+    for (int i = r0; i < r1; i += 4) {
+        float v[4][4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = i + u < r1 ? src[(size_t)(i + u) * ncols] : 0.f;
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
-        }
+            for (int q = 0; q < 4; ++q)
+                v[u][q] = (i + u < r1 && c0 + 64 * q < ncols) ? src[(size_t)(i + u) * ncols + c0 + 64 * q] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] += v[u][q];
     }
-    part[slice][lane] = acc;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[slice][lane + 64 * q] = acc[q];
     __syncthreads();
-    if (slice == 0 && c < ncols)
-        out[(size_t)e * ncols + c] = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (threadIdx.x < 256 && c < ncols) {
+        float sum = part[0][threadIdx.x];
+        for (int q = 1; q < nsl; ++q) sum += part[q][threadIdx.x];
+        out[(size_t)e * ncols + c] = sum;
+    }
+}
+
+// Slices per workgroup of colsum_finish: many when an expert has many partial rows on average (small
+// tiles, few experts), few when it has few: wide workgroups with mostly idle wavefronts cost more
+// than they save there.
+inline int finish_slices(size_t partial_rows, int E) {
+    return partial_rows / (size_t)E >= 64 ? kFinishSlices : 4;
 }
 
 // Backward prologue and the fc2 bias gradient in one pass (ESS, Sec. 3.1 item 2; Table 5 row 4):
@@ -346,7 +364,7 @@ hipError_t launch_bwd_prologue(const MoeDims& D, const T* dY, const T* o,
                                D.k, dY, o, perm, offsets, D.E, gate, dout, dgate, partial, R);
         }
         ProfScope ps(st, "colsum_db2");
-        hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(D.d, 64)), dim3(256), 0, st, partial, D.d,
+        hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(D.d, 256)), dim3(64 * finish_slices((size_t)D.A / R + D.E, D.E)), 0, st, partial, D.d,
                            D.E, R, 1, offsets, db2);
         return hipGetLastError();
     }
@@ -366,7 +384,7 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
     ProfScope ps(st, ncols == D.d ? "colsum_db2" : "colsum_db1");
     hipLaunchKernelGGL(colsum_stage1<T>, dim3(max_tiles, cb), dim3(256), 0, st, src, ncols, D.E,
                        offsets, partial);
-    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 64)), dim3(256), 0, st, partial, ncols, D.E,
+    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 256)), dim3(64 * finish_slices((size_t)D.A / kColsumRows + D.E, D.E)), 0, st, partial, ncols, D.E,
                        kColsumRows, 1, offsets, out);
     return hipGetLastError();
 }
@@ -374,7 +392,7 @@ hipError_t launch_segment_colsum(const MoeDims& D, const T* src, int ncols, cons
 hipError_t launch_tile_colsum_finish(const MoeDims& D, const float* partial, int ncols,
                                      const int32_t* offsets, float* out, hipStream_t st) {
     ProfScope ps(st, "colsum_db1");
-    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 64)), dim3(256), 0, st, partial, ncols,
+    hipLaunchKernelGGL(colsum_finish, dim3(D.E, ceil_div(ncols, 256)), dim3(64 * finish_slices(((size_t)D.A / gemm_row_tile() + D.E) * gemm_colpart_rows_per_tile(), D.E)), 0, st, partial, ncols,
                        D.E, gemm_row_tile(), gemm_colpart_rows_per_tile(), offsets, out);
     return hipGetLastError();
 }
