@@ -256,7 +256,9 @@ __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& til
 // lists: they are part of what the forward pass leaves in the workspace), so that a
 // workgroup finds its tile with two scalar loads instead of a walk over all experts (which cost a
 // 256x256 tile of a d = 2048 contraction about a tenth of its time, with the CU idle meanwhile).
-//   wl[0] = number of row tiles, wl[1] = number of token-contraction items, wl[2..3] unused
+//   wl[0] = number of row tiles, wl[1] = number of token-contraction items,
+//   wl[2], wl[3] = 1 when the fused backward grid of the second / first linear layer starts with
+//                  its token contraction (see gemm_bf16_pair), else 0
 //   wl[4 + 4 t ...]            row tile t:  expert, first perm row, rows (1..bm), unused
 //   wl[4 + 4 rt_cap + 4 i ...] item i:      expert, first perm row, end perm row, split-K slot
 // Row tiles are numbered expert-major (tiles never straddle experts; experts without rows have
@@ -265,7 +267,7 @@ __device__ __forceinline__ void grouped_tile(int local, int tm, int tn, int& til
 // means the expert is one chunk and its tile goes straight to the output.
 __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restrict__ offsets, int E,
                                                         int bm, int L, int32_t* __restrict__ wl,
-                                                        int rt_cap) {
+                                                        int rt_cap, int d, int f) {
     __shared__ int s_t[1024], s_c[1024], s_s[1024];
     const int e = threadIdx.x;
     int b = 0, n = 0, nt = 0, nc = 0, ns = 0;
@@ -293,7 +295,16 @@ __global__ __launch_bounds__(1024) void build_worklists(const int32_t* __restric
         int32_t* q = items + 4 * (c0 + c);
         q[0] = e; q[1] = b + c * L; q[2] = min(b + n, b + c * L + L); q[3] = nc > 1 ? slot0 + c : -1;
     }
-    if (e == E - 1) { wl[0] = s_t[e]; wl[1] = s_c[e]; wl[2] = 0; wl[3] = 0; }
+    if (e == E - 1) {
+        // the longest token-contraction item, in rows; a fused backward grid starts with the token
+        // contraction when that item runs at least eight times as long as a tile of the row GEMM it
+        // shares the grid with (K = d for the second layer's, K = f for the first layer's)
+        int longest = 0;
+        for (int q = 0; q < E; ++q) longest = max(longest, min(L, offsets[q + 1] - offsets[q]));
+        wl[0] = s_t[e]; wl[1] = s_c[e];
+        wl[2] = longest >= 8 * d ? 1 : 0;
+        wl[3] = longest >= 8 * f ? 1 : 0;
+    }
 }
 
 // Row-offset table of the gathered token contraction (WGRAD1 reads x[perm[p] / k] for perm
@@ -955,13 +966,21 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16(GemmArgs g) {
 
 // Two independent contractions in one grid (the paper's fused backward kernel, Sec. 3.2 "Fused
 // Kernel in Backward Propagation": the input gradient and the weight gradient of one linear layer
-// do not depend on each other): slots [0, items_a) are contraction OPA's, the rest OPB's, so the
-// tail of one fills with tiles of the other.  items_a is a multiple of 8 (XCD mapping).
+// do not depend on each other), so the tail of one fills with tiles of the other.  Both item counts
+// are multiples of 8 (XCD mapping).  Workgroups start roughly in slot order, so the contraction
+// with the longer tiles should come first: normally the row GEMM OPA (slots [0, items_a)), but the
+// token contraction OPB when routing is so skewed that one expert's chunk runs many times longer
+// than a row-GEMM tile (flag `order` of the work-list header, set by build_worklists; with Zipf
+// routing at C5's shape the largest expert's tiles run 1582 K-blocks against 32 or 128).
 template <int BM, int BN, int WM, int WN, int OPA, int OPB, bool F16 = false>
-__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_pair(GemmArgs ga, GemmArgs gb, int items_a) {
+__global__ __launch_bounds__(WM * WN * 64, 1) void gemm_bf16_pair(GemmArgs ga, GemmArgs gb, int items_a, int order) {
     const int item = (int)blockIdx.x;
-    if (item < items_a) gemm_tile<BM, BN, WM, WN, OPA, HEXA_ACT_GELU_TANH, F16>(ga, item);
-    else gemm_tile<BM, BN, WM, WN, OPB, HEXA_ACT_GELU_TANH, F16>(gb, item - items_a);
+    const int items_b = (int)gridDim.x - items_a;
+    const bool b_first = ga.worklist[order] != 0;
+    const bool is_b = b_first ? item < items_b : item >= items_a;
+    const int local = b_first ? (is_b ? item : item - items_b) : (is_b ? item - items_a : item);
+    if (is_b) gemm_tile<BM, BN, WM, WN, OPB, HEXA_ACT_GELU_TANH, F16>(gb, local);
+    else gemm_tile<BM, BN, WM, WN, OPA, HEXA_ACT_GELU_TANH, F16>(ga, local);
 }
 
 // Second stage of the split token contraction, plus exact zeros for experts without tokens.
@@ -1026,7 +1045,8 @@ void launch_pair(const MoeDims& D, const GemmArgs& ga, const GemmArgs& gb, hipSt
     const int items_b = kXcds * ceil_div(tmn, kXcds) * (D.A / gb.chunk_len + D.E);
     {
         ProfScope ps(st, label);
-        hipLaunchKernelGGL(kern, dim3(items_a + items_b), dim3(WM * WN * 64), lds, st, ga, gb, items_a);
+        hipLaunchKernelGGL(kern, dim3(items_a + items_b), dim3(WM * WN * 64), lds, st, ga, gb, items_a,
+                           OPB == OP_WGRAD2 ? 2 : 3);
     }
     ProfScope ps(st, label_fin);
     const size_t mn = (size_t)gb.M * gb.N;
@@ -1093,7 +1113,7 @@ size_t gemm_worklist_ints(const MoeDims& D) {
 static void launch_worklists(const MoeDims& D, const hexa_moe_idx& idx, const MoeWorkspace& ws, hipStream_t st) {
     ProfScope ps(st, "worklists");
     hipLaunchKernelGGL(build_worklists, dim3(1), dim3(1024), 0, st, idx.offsets, D.E, TBM,
-                       wgrad_chunk_len(D), ws.worklist, worklist_rt_cap(D));
+                       wgrad_chunk_len(D), ws.worklist, worklist_rt_cap(D), D.d, D.f);
 }
 
 // Upper bound on split-K slots: only experts with more than one chunk use slots, and
