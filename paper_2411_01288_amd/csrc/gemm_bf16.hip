@@ -1000,13 +1000,25 @@ __global__ __launch_bounds__(256) void wgrad_finish(const int32_t* __restrict__ 
     }
     float4* dst = reinterpret_cast<float4*>(out + (size_t)e * mn);
     const size_t n4 = mn / 4;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const size_t stride = (size_t)gridDim.x * 256;
+    // four elements per thread and pass, their loads issued together (one at a time, the few
+    // workgroups of a split expert are a chain of memory latencies)
+    for (size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x; i0 < n4; i0 += 4 * stride) {
+        float4 s[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int c = 0; c < nch; ++c) {
-            const float4 v = reinterpret_cast<const float4*>(kpart + (size_t)(slot + c) * mn)[i];
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            const float4* src = reinterpret_cast<const float4*>(kpart + (size_t)(slot + c) * mn);
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = i0 + u * stride < n4 ? src[i0 + u * stride] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { s[u].x += v[u].x; s[u].y += v[u].y; s[u].z += v[u].z; s[u].w += v[u].w; }
         }
-        dst[i] = s;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u * stride < n4) dst[i0 + u * stride] = s[u];
     }
 }
 
