@@ -697,10 +697,39 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
         }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA + NIB) : "memory");
     __syncthreads();
-    _Pragma("unroll") for (int r = 0; r < NRD; ++r) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, r);
-
     int sa = 0, sb = 1;                           // slots of A(j), B(j)
     int j = 0;
+    if constexpr (!TOKENS) {
+        // A wave whose 128 rows all lie past the segment's end (the lower half of a tail tile with
+        // at most 128 rows) has nothing to multiply: it keeps its share of the staging requests and
+        // the barriers, and skips the fragment reads, the MFMAs and the epilogue.  The time of the
+        // tile is the other waves'; what is saved is energy, which is what this part runs short of.
+        if (__builtin_amdgcn_readfirstlane(mvalid - wm * TM) <= 0) {
+            do {
+                const int sa1 = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
+                const int sb1 = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
+                const int sa2 = sa + 4 >= NSLOT ? sa + 4 - NSLOT : sa + 4;
+                const uint32_t a2 = smem0 + (uint32_t)(sa2 * SLOT), b2 = smem0 + (uint32_t)(sa * SLOT);
+                const uint32_t kreq = (uint32_t)min(j + 2, klast);
+                _Pragma("unroll") for (int o = 0; o < NIA; ++o) { PREP_A(a2, o); asm volatile("s_nop 0"); LOAD_A(kreq, o); }
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIA) : "memory");
+                __syncthreads();
+                _Pragma("unroll") for (int o = 0; o < NIB; ++o) { PREP_B(b2, o); asm volatile("s_nop 0"); LOAD_B(kreq, o); }
+                sa = sa1; sb = sb1;
+            } while (++j < nk);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();   // the barrier in front of the other waves' epilogue
+            if constexpr (OP == OP_DGRAD2) {   // this wave's column-sum partials: no rows, zeros
+                const int col = wn * TN + 2 * lane;
+                if (col < nvalid)
+                    *reinterpret_cast<float2*>(g.colpart + (size_t)(row_tile * WM + wm) * (size_t)g.N + n0 + col) =
+                        make_float2(0.f, 0.f);
+            }
+            return;
+        }
+    }
+    _Pragma("unroll") for (int r = 0; r < NRD; ++r) READ_ONE(fa0, fb0, smem, smem + SLOT, 0, r);
+
     do {
         uint8_t* abase = smem + sa * SLOT;
         uint8_t* bbase = smem + sb * SLOT;
