@@ -898,12 +898,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         wb + row * RPB + ((((lane >> 2) ^ row)) << 4) + (lane & 3) * 4);
             }
         };
-        auto band_stores = [&](int i) __attribute__((always_inline)) {
+        auto band_store_one = [&](int i, int t) __attribute__((always_inline)) {
+            const int soff = (i * BAND + RPI_O * t) * ldo_b;
+            __builtin_amdgcn_raw_buffer_store_b128(d0[t], ro0, ovoff[t], soff, 0);
+            if constexpr (OP == OP_FC1) __builtin_amdgcn_raw_buffer_store_b128(d1[t], ro1, ovoff[t], soff, 0);
+        };
+        auto band_stores = [&](int i, bool with_stores) __attribute__((always_inline)) {
+            if (with_stores) {
 #pragma unroll
-            for (int t = 0; t < NST; ++t) {
-                const int soff = (i * BAND + RPI_O * t) * ldo_b;
-                __builtin_amdgcn_raw_buffer_store_b128(d0[t], ro0, ovoff[t], soff, 0);
-                if constexpr (OP == OP_FC1) __builtin_amdgcn_raw_buffer_store_b128(d1[t], ro1, ovoff[t], soff, 0);
+                for (int t = 0; t < NST; ++t) band_store_one(i, t);
             }
             if constexpr (OP == OP_DGRAD2) {
 #pragma unroll
@@ -972,13 +975,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                         *reinterpret_cast<u32x2*>(wb + off) = d;
                     }
                 }
+                // the previous band's stores go out one at a time between the blocks of this band's
+                // arithmetic: issued in a row behind it they fill the address queue of the texture
+                // unit and the wave waits (5 % of fc1's cycles)
+                if (i > 0 && j % (FN / NST) == FN / NST - 1) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    band_store_one(i - 1, j / (FN / NST));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
-            // -- LDS band -> global rows: instruction t covers 1024/RPB rows, a lane one chunk
-            if (i > 0) band_stores(i - 1);
+            if (i > 0) band_stores(i - 1, false);   // (DGRAD2: the previous band's column sums)
         }
         band_reads((FM - 1) & 1);
-        band_stores(FM - 1);
+        band_stores(FM - 1, true);
         if constexpr (OP == OP_DGRAD2) {
             const int col = wcol0 + 2 * lane;
             if (col < nvalid)
