@@ -946,9 +946,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
                     v[0] += b0; v[1] += b1; v[2] += b2; v[3] += b3;
                 }
                 if constexpr (OUT_F32) {
+                    // straight from the accumulation registers (an LDS store may take its data from
+                    // them; through ordinary registers it is 256 more copies per wave and tile)
                     const int c = col >> 2;
-                    *reinterpret_cast<float4*>(wb + l16 * RPB + ((c ^ l16) << 4)) =
-                        make_float4(v[0], v[1], v[2], v[3]);
+                    const uint32_t la = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)(wb + l16 * RPB + ((c ^ l16) << 4));
+                    asm volatile("ds_write_b128 %0, %1" : : "v"(la), "a"(acc[i][j]) : "memory");
                 } else {
                     const int c = col >> 3;
                     const uint32_t off = (uint32_t)(l16 * RPB + ((c ^ l16) << 4) + (grp & 1) * 8);
