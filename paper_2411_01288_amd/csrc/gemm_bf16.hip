@@ -138,9 +138,11 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
 // one instruction: lane l's 16 bytes at (voff + soff) land at lds + 16*l; lds is wave-uniform.
 // Written as inline assembly on purpose: the compiler then neither tracks these loads in vmcnt nor
 // assumes that every later LDS read may alias them (which made it wait for the whole stage in
-// front of each fragment read).  The kernel waits explicitly: one "s_waitcnt vmcnt(0)" in front of
-// the barrier that hands the stage buffer over, and no other vector-memory load is in flight
-// inside the K loop.  M0 carries the LDS address (one wait state before the load reads it).
+// front of each fragment read).  The kernel counts its own requests and waits explicitly (one
+// "s_waitcnt vmcnt(n)" in front of the barrier that publishes a block, n = the requests that may
+// still be in flight); the only other vector-memory loads inside the K loop are the row-offset
+// loads of the gathered token contraction, inline assembly too and counted with them.  M0 carries
+// the LDS address (one wait state before the load reads it).
 __device__ __forceinline__ void dtl16(rsrc_t r, uint8_t* lds, uint32_t voff, uint32_t soff) {
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
         (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds);
@@ -774,7 +776,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int item) {
     // need before the epilogue reads the accumulators: 16 idle cycles cover the 4-pass MFMA)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 7\n\ts_nop 7" ::: "memory");
     // pin every accumulator to its accumulation register at the loop exit (keeps the register
-    // allocator from shuffling them where the loop and the zero-trip path meet)
+    // allocator from shuffling them between the loop and the epilogue)
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
