@@ -31,7 +31,7 @@
  *   - HEXA_BF16 and HEXA_F16 (the MFMA paths) need d % 64 == 0 and f % 64 == 0
  *     (the K loop of the contraction kernels runs in blocks of 64, one 128-byte
  *     line per operand row; the paper's kernels likewise assume feature sizes
- *     divisible by the tile, App. B), T*d*2 <= 2^32 - 2^16, d*f*2 < 2^32 and
+ *     divisible by the tile, App. B), (T+1)*d*2 < 2^32, d*f*2 < 2^32 and
  *     256*max(d,f)*4 < 2^31 (32-bit byte offsets inside x, inside one expert's
  *     weight matrix and inside one 256-row tile of an activation or gradient
  *     matrix);

@@ -25,7 +25,7 @@ hexa_status hexa_check_shape(const hexa_moe_shape* s, MoeDims* D) {
         // one 256-row tile of any activation matrix with 32-bit byte offsets; the output window of a
         // tile (256 rows of fp32 at most) must stay below 2^31 bytes, the offset that masks a lane
         const unsigned long long wide = (unsigned long long)(s->d_model > s->d_ff ? s->d_model : s->d_ff);
-        if ((unsigned long long)s->T * s->d_model * 2ull > 0xffff0000ull ||   // (+ a tile row must still fit behind the last row)
+        if (((unsigned long long)s->T + 1ull) * s->d_model * 2ull > 0xffffffffull ||   // x and one more row: the offset that masks a gathered row points there
             (unsigned long long)s->d_model * s->d_ff * 2ull > 0xffffffffull ||
             256ull * wide * 4ull > 0x7fffffffull)
             return HEXA_ERR_UNSUPPORTED;

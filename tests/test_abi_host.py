@@ -37,7 +37,7 @@ def test_size_queries_and_shape_validation(B):
     assert B.workspace_bytes(ok) > 4096 * 2 * 1536 * 2 * 2
     assert B.index_scratch_bytes(ok) >= 8 * 4
     f32 = B.make_shape(7, 5, 3, 2, 1, "f32")            # fp32 takes any positive sizes
-    assert B.workspace_bytes(B.make_shape((1 << 19) - 8, 4096, 64, 4, 1, "bf16")) > 0   # T*d*2 = 2^32 - 2^16: the largest x
+    assert B.workspace_bytes(B.make_shape((1 << 19) - 2, 4096, 64, 4, 1, "bf16")) > 0   # (T+1)*d*2 = 2^32 - 8192: the largest x
     assert B.workspace_bytes(f32) > 0
     for bad in (B.make_shape(0, 64, 64, 4, 1, "bf16"), B.make_shape(8, 64, 64, 0, 1, "bf16"),
                 B.make_shape(8, 64, 64, 4, 0, "bf16"), B.make_shape(8, -64, 64, 4, 1, "bf16"),
@@ -46,7 +46,7 @@ def test_size_queries_and_shape_validation(B):
                 B.make_shape(8, 60, 64, 4, 1, "bf16"),             # bf16 needs multiples of 64
                 B.make_shape(8, 64, 1 << 23, 4, 1, "bf16"),        # 256 rows of d_ff exceed 32-bit byte offsets
                 B.make_shape(1 << 21, 64, 1 << 21, 4, 1, "bf16"),  # one 256-row fp32 output window reaches 2^31 bytes
-                B.make_shape((1 << 19) - 1, 4096, 64, 4, 1, "bf16"),  # x leaves no room behind its last row (T*d*2 > 2^32 - 2^16)
+                B.make_shape((1 << 19) - 1, 4096, 64, 4, 1, "bf16"),  # x and one more row reach 2^32 bytes
                 B.Shape(8, 64, 64, 4, 1, 7, 0),                    # unknown dtype
                 B.make_shape(8, 64, 64, 4, 1, "bf16", 3)):         # unknown activation
         assert B.workspace_bytes(bad) == 0 and B.index_scratch_bytes(bad) == 0
